@@ -1,0 +1,12 @@
+"""CPU fp64 oracle of the chunked-prefill decoder layer.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path (the HIP library and its
+Python binding) may import, call or link this package; it exists so that tests,
+the smoke check and the benchmark's CPU-baseline leg have an independent,
+obviously-correct statement of what the layer computes.
+"""
+from .decoder_layer import (  # noqa: F401
+    LayerParams, rmsnorm, rope_angles, rope, silu, causal_gqa_attention,
+    layer_forward, layer_forward_rows, ChunkedPrefill, prefill_batch, rel_fro,
+)
+from .brute_force import attention_loops  # noqa: F401
