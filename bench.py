@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked-prefill decoder-layer path on one MI355X.
+
+A step is one pass of the whole hot path over the benchmark workload: a synthetic 8192-token multi-image prompt
+(6 images of 1024 embedding rows interleaved with text spans) prefilled in 4 chunks under a 2048-token budget through
+4 stacked 7B-shaped decoder layers, i.e. 16 rs_prefill_chunk calls with the KV prefix growing 0 -> 6144.
+`value` = layer-tokens per second (tokens x layers / time), inputs and weights resident in HBM.
+
+Prints ONE JSON line (see README / DESIGN for the fields): metric, value, ms_per_step, roofline of the dominant
+kernel (the fused gate/up + SwiGLU GEMM, timed live with HIP events on its own stream inside the timed region), and
+the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(wl, w0, x, rows: int):
+    """The oracle as it stands, one layer over the first `rows` rows of the same prompt, on the host cores."""
+    import numpy as np
+    from oracle import LayerParams, layer_forward
+    threads = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+        if blas:
+            threads = max(blas)
+    except Exception:
+        pass
+    p = LayerParams.from_arrays(wl.shape, w0)
+    t0 = time.perf_counter()
+    layer_forward(x[:rows], p)
+    dt = time.perf_counter() - t0
+    flops = wl.shape.linear_flops_per_token() * rows + wl.shape.attn_flops(rows, 0)
+    return {"value": rows / dt, "unit": "layer-tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 oracle layer_forward, layer 0, first {rows} rows of the same prompt (P=0), {dt:.2f} s, "
+                      f"{flops / dt / 1e9:.1f} GFLOP/s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2509_24381_amd import runner
+    from paper_2509_24381_amd.binding import STEPS
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.workload(3)
+    sh = wl.shape
+    weights = [wl.weights(l) for l in range(wl.n_layers)]
+    x = wl.prompt()
+    chunks = wl.chunks()
+    stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=1, max_pos=wl.n_tokens)
+    w0 = weights[0]
+    del weights
+    kv = stack.new_cache(wl.n_tokens)
+    x_dev = runner.to_device_bf16(x)
+
+    def step():
+        kv.reset()
+        stack.prefill_prompt(x_dev, chunks, kv)
+
+    calls_per_step = len(chunks) * wl.n_layers
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stack.ctx.profile_enable("gate_up_gemm", calls_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gu_ms, gu_n = stack.ctx.profile_read()
+    stack.ctx.profile_enable(None)
+
+    layer_tokens = wl.n_tokens * wl.n_layers
+    flops_step = wl.n_layers * sum(sh.linear_flops_per_token() * (b - a) + sh.attn_flops(b - a, a) for a, b in chunks)
+    ms_per_step = dt / args.steps * 1e3
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    gu_flops = 2.0 * wl.budget * sh.hidden * 2 * sh.mlp_inter      # per launch: [2048, H] x [2I, H]^T
+    gu_avg_ms = gu_ms / max(gu_n, 1)
+    gu_tflops = gu_flops / (gu_avg_ms * 1e-3) / 1e12
+    out = {
+        "metric": "chunked-prefill tokens/s per layer @7B shape, 2048 budget; MFMA util % of peak",
+        "value": layer_tokens / (ms_per_step * 1e-3),
+        "unit": "layer-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.n_layers, "prompt_tokens": wl.n_tokens, "token_budget": wl.budget,
+                   "calls_per_step": calls_per_step, "shape": "hidden 3584, 28 q / 4 kv heads, head_dim 128, mlp 18944"},
+        "tflops": tflops,
+        "mfma_frac_whole_path": tflops / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"kernel": "gemm_bf16_256x256_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
+                     "bound": "mfma", "achieved": gu_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "avg_ms": gu_avg_ms, "launches": gu_n},
+    }
+
+    if args.breakdown:
+        bd = {}
+        for name in STEPS:
+            stack.ctx.profile_enable(name, calls_per_step)
+            step()
+            torch.cuda.synchronize()
+            ms, n = stack.ctx.profile_read()
+            bd[name] = ms / max(n, 1)
+        stack.ctx.profile_enable(None)
+        out["breakdown_avg_ms_per_call"] = bd
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, w0, x, args.cpu_rows)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,174 @@
+/*
+ * rserve_prefill.h -- C ABI of the chunked-prefill decoder-layer library for AMD MI355X (gfx950).
+ *
+ * What the library computes.  RServe (arXiv 2509.24381) schedules the language model's prefill
+ * in token-budgeted chunks; its Algorithm 2 (section 3.3) ends in BatchExecute(S), one forward
+ * pass of the language model over a micro-batch S that holds the schedulable tokens of one or
+ * more requests.  Chunked prefill (section 2.1.1 and section 2.2.1) means: the prompt is split
+ * into chunks that are processed one after another, and a chunk depends on earlier chunks only
+ * through the KV cache they left behind.  This library is that forward pass for ONE decoder
+ * layer at a time:
+ *
+ *     h = rmsnorm(x) -> q,k,v = h Wqkv^T (+b) -> RoPE(q,k) at absolute positions P..P+T-1
+ *     -> append k~,v to the request's KV cache -> causal GQA attention of the chunk against the
+ *     whole cache -> r = x + o Wo^T -> y = r + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T,  h2 = rmsnorm(r)
+ *
+ * with bf16 storage (inputs, weights, KV cache, outputs) and fp32 accumulation.  The paper does
+ * not spell out the layer; it is the pre-norm decoder block of the model family the paper serves
+ * (section 4.1.1), with sequential 1-D rotary positions.
+ *
+ * Conventions shared by every call
+ *  - Every `void*` named dev / documented "device" is GPU memory owned by the CALLER (typically a
+ *    PyTorch tensor).  The library owns only host-side handles (rs_ctx, rs_kv), pinned host staging
+ *    for per-call descriptors, and one device buffer it allocates in rs_ctx_create (the RoPE
+ *    cos/sin table).  rs_prefill_* allocate nothing.
+ *  - Slabs (weights, KV, workspace) must be 256-byte aligned; x and y 16-byte aligned.
+ *  - All work is enqueued on the caller's HIP stream (`hip_stream`, a hipStream_t passed as
+ *    void*, NULL = the null stream) and the call returns without waiting.  Host-side state
+ *    (cache lengths) is advanced at enqueue time.  The caller orders streams; two calls that use
+ *    the same rs_kv, the same workspace or the same rs_ctx concurrently on different streams race.
+ *  - Errors are decided on the host BEFORE anything is launched; on any status other than RS_OK
+ *    nothing was enqueued and no state changed (RS_EHIP excepted: a launch itself failed).
+ *  - bf16 matrices are row-major.  "torch layout" for a weight means [out_features, in_features].
+ */
+#ifndef RSERVE_PREFILL_H
+#define RSERVE_PREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rs_status {
+    RS_OK = 0,
+    RS_EINVAL = -1,     /* null / misaligned pointer, negative size, bad layer index, duplicate request, shape the kernels do not support */
+    RS_ECAPACITY = -2,  /* chunk does not fit the KV cache capacity or the RoPE table (max_pos) */
+    RS_EWORKSPACE = -3, /* workspace smaller than rs_workspace_bytes() for this call */
+    RS_ESTATE = -4,     /* handle used with a context it was not created for */
+    RS_EHIP = -5        /* a HIP runtime call failed; see rs_last_error() */
+} rs_status;
+
+/* Shape of one decoder layer and the limits of one call. */
+typedef struct rs_layer_cfg {
+    int hidden;               /* H; multiple of 256 */
+    int n_q_heads;            /* Hq */
+    int n_kv_heads;           /* Hkv; divides Hq */
+    int head_dim;             /* d; 64 or 128 */
+    int mlp_inter;            /* I; multiple of 128 */
+    float rms_eps;            /* added to mean(x^2) inside the square root */
+    float rope_theta;         /* RoPE base; angle of pair j at position n is n * theta^(-2j/d) */
+    int qkv_bias;             /* nonzero: rs_layer_weights.b_qkv is used */
+    int max_tokens_per_call;  /* upper bound on the rows of one rs_prefill_* call (the token budget B of Algorithm 2) */
+    int max_requests;         /* upper bound on R in rs_prefill_batch */
+    int max_pos;              /* RoPE table length: cache length after any call must stay <= max_pos */
+} rs_layer_cfg;
+
+/* Device pointers to one layer's parameters (bf16).
+ * In torch layout: ln1_g[H], w_qkv[(Hq+2Hkv)*d, H] = rows of Wq, then Wk, then Wv, b_qkv[(Hq+2Hkv)*d] or NULL,
+ * w_o[H, Hq*d], ln2_g[H], w_gate_up[2I, H] = rows of W_gate then W_up, w_down[H, I].
+ * rs_prefill_* take the PACKED form produced by rs_weights_pack (same struct, pointers into the packed slab). */
+typedef struct rs_layer_weights {
+    const void* ln1_g;
+    const void* w_qkv;
+    const void* b_qkv;
+    const void* w_o;
+    const void* ln2_g;
+    const void* w_gate_up;
+    const void* w_down;
+} rs_layer_weights;
+
+typedef struct rs_ctx rs_ctx; /* layer shape + RoPE table + descriptor staging; host handle */
+typedef struct rs_kv rs_kv;   /* one request's KV cache over n_layers layers; host handle over caller-owned device memory */
+
+/* Create / destroy a context for one layer shape on the current HIP device.
+ * Allocates the RoPE cos/sin table (max_pos * d/2 * 8 bytes of device memory) and pinned staging for
+ * per-call request descriptors.  RS_EINVAL if the shape is outside what the kernels support (see rs_layer_cfg).
+ * On a host without a GPU the context is still created (host-only): every argument check works, and any call that
+ * would have to launch returns RS_EHIP. */
+rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out);
+void rs_ctx_destroy(rs_ctx* ctx);
+
+/* One-time weight repack, off the hot path.  `src` holds torch-layout device pointers; `dst` is a caller-owned
+ * device slab of rs_weights_packed_bytes() bytes; `packed` receives pointers into `dst` in the layout the
+ * kernels read (gate and up rows interleaved in blocks so SwiGLU can be applied inside the GEMM).
+ * After the call completes on `hip_stream` the torch-layout tensors may be freed. */
+size_t rs_weights_packed_bytes(const rs_ctx* ctx);
+rs_status rs_weights_pack(rs_ctx* ctx, const rs_layer_weights* src, void* dst, size_t dst_bytes,
+                          rs_layer_weights* packed, void* hip_stream);
+
+/* KV cache (the per-request state chunked prefill builds, section 2.2.1).  The slab layout is private; capacity is
+ * fixed at allocation.  Each layer keeps its own length so that layers 0..L-1 can be run in turn for a chunk.
+ *   rs_kv_bytes      bytes of device memory needed for n_layers layers of capacity_tokens tokens.
+ *   rs_kv_alloc      wraps caller-owned device memory `dev_mem` (>= rs_kv_bytes, 256-byte aligned); lengths start at 0.
+ *   rs_kv_free       frees the host handle only.
+ *   rs_kv_len        cached tokens of `layer`, or -1 on a bad argument.
+ *   rs_kv_reset      all lengths := 0.
+ *   rs_kv_truncate   length of `layer` := n_tokens (0 <= n_tokens <= current length): drops the newest tokens.
+ *   rs_kv_export     copies the first rs_kv_len tokens to canonical bf16 [len][Hkv][d] arrays (post-RoPE K, V).
+ *   rs_kv_import     loads n_tokens canonical rows as the cache content of `layer` and sets its length. */
+size_t rs_kv_bytes(const rs_ctx* ctx, int n_layers, int capacity_tokens);
+rs_status rs_kv_alloc(rs_ctx* ctx, int n_layers, int capacity_tokens, void* dev_mem, size_t bytes, rs_kv** out);
+void rs_kv_free(rs_kv* kv);
+int rs_kv_len(const rs_kv* kv, int layer);
+int rs_kv_capacity(const rs_kv* kv);
+rs_status rs_kv_reset(rs_kv* kv);
+rs_status rs_kv_truncate(rs_kv* kv, int layer, int n_tokens);
+rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out_dev, void* v_out_dev, void* hip_stream);
+rs_status rs_kv_import(rs_kv* kv, int layer, const void* k_dev, const void* v_dev, int n_tokens, void* hip_stream);
+
+/* Bytes of device workspace a call with up to max_tokens rows and max_requests requests needs. */
+size_t rs_workspace_bytes(const rs_ctx* ctx, int max_tokens, int max_requests);
+
+/* One chunk of one request through one layer (chunked prefill, section 2.2.1).
+ *   x   device bf16 [T, H]: the chunk's rows (image-embedding or text-embedding rows alike), prompt order.
+ *   y   device bf16 [T, H]: layer output; may alias x.
+ * With P = rs_kv_len(kv, layer): rows take positions P..P+T-1, their post-RoPE K and V are appended at [P, P+T),
+ * row i attends to cache entries 0..P+i, and the layer's length becomes P+T.  T = 0 is a no-op.
+ * RS_ECAPACITY if P+T exceeds the cache capacity or max_pos; RS_EINVAL if T > max_tokens_per_call. */
+rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv,
+                           const void* x_dev, int T, void* y_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* One micro-batch of R requests through one layer (the set S of Algorithm 2, section 3.3).
+ *   kvs[i], chunk_lens[i]  host arrays: request i contributes chunk_lens[i] >= 0 rows this round.
+ *   x   device bf16 [sum chunk_lens, H]: rows packed in request order, each request's rows contiguous, prompt order.
+ *   y   device bf16, same shape; may alias x.
+ * Each request behaves exactly as in rs_prefill_chunk against its own cache; requests do not interact.
+ * The same rs_kv may not appear twice (RS_EINVAL).  sum chunk_lens must be <= max_tokens_per_call, R <= max_requests. */
+rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int layer,
+                           rs_kv* const* kvs, const int* chunk_lens, int R,
+                           const void* x_dev, void* y_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Measurement hook.  The steps of one rs_prefill_* call, in launch order: */
+typedef enum rs_step {
+    RS_STEP_RMSNORM_1 = 0,
+    RS_STEP_QKV_GEMM = 1,
+    RS_STEP_ROPE_APPEND_K = 2,
+    RS_STEP_APPEND_V = 3,
+    RS_STEP_ATTENTION = 4,
+    RS_STEP_O_GEMM = 5,      /* includes its split-K reduction when one is used */
+    RS_STEP_RMSNORM_2 = 6,
+    RS_STEP_GATE_UP_GEMM = 7,
+    RS_STEP_DOWN_GEMM = 8,   /* includes its split-K reduction when one is used */
+    RS_STEP_COUNT = 9
+} rs_step;
+/* rs_profile_enable(ctx, step, n): from now on the first n launches of `step` are bracketed by two HIP events recorded
+ * on the call's own stream (step = -1 switches the hook off).  rs_profile_read waits for the recorded events, returns
+ * the summed elapsed milliseconds and the number of launches measured, and restarts the count.  Events are created in
+ * rs_profile_enable, never inside rs_prefill_*. */
+rs_status rs_profile_enable(rs_ctx* ctx, int step, int max_launches);
+rs_status rs_profile_read(rs_ctx* ctx, double* total_ms, int* launches);
+
+/* Message of the most recent failing call on this thread (never NULL). */
+const char* rs_last_error(void);
+
+/* Library version, for the binding's sanity check. */
+int rs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSERVE_PREFILL_H */

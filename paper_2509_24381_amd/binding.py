@@ -1,0 +1,269 @@
+"""ctypes binding of the C ABI in include/rserve_prefill.h.
+
+Argument marshalling only: every step of the layer runs in the HIP library.  PyTorch is used for device
+memory (`torch.empty(..., device="cuda")`, `.data_ptr()`) and for the current HIP stream; nothing here
+computes.  If the shared library is missing the import of this module still works, but every use raises
+RsError: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "librserve_prefill.so"
+
+STATUS = {0: "RS_OK", -1: "RS_EINVAL", -2: "RS_ECAPACITY", -3: "RS_EWORKSPACE", -4: "RS_ESTATE", -5: "RS_EHIP"}
+
+# every symbol include/rserve_prefill.h declares
+EXPORTED_SYMBOLS = (
+    "rs_ctx_create", "rs_ctx_destroy", "rs_weights_packed_bytes", "rs_weights_pack", "rs_kv_bytes", "rs_kv_alloc",
+    "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
+    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_last_error", "rs_version",
+    "rs_profile_enable", "rs_profile_read",
+)
+
+STEPS = ("rmsnorm_1", "qkv_gemm", "rope_append_k", "append_v", "attention", "o_gemm", "rmsnorm_2", "gate_up_gemm",
+         "down_gemm")
+
+
+class RsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+        self.status_name = STATUS.get(status, str(status))
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("hidden", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("mlp_inter", C.c_int), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qkv_bias", C.c_int),
+                ("max_tokens_per_call", C.c_int), ("max_requests", C.c_int), ("max_pos", C.c_int)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("ln1_g", C.c_void_p), ("w_qkv", C.c_void_p), ("b_qkv", C.c_void_p), ("w_o", C.c_void_p),
+                ("ln2_g", C.c_void_p), ("w_gate_up", C.c_void_p), ("w_down", C.c_void_p)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(PKG_DIR, _LIB_NAME)
+
+
+def load_library():
+    """Loads librserve_prefill.so (built in-tree by paper_2509_24381_amd.build) and declares the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RsError(-5, f"{path} is not built; run `python -m paper_2509_24381_amd.build` (there is no fallback path)")
+    lib = C.CDLL(path)
+    vp, sz, i = C.c_void_p, C.c_size_t, C.c_int
+    proto = {
+        "rs_ctx_create": (i, [C.POINTER(_Cfg), C.POINTER(vp)]),
+        "rs_ctx_destroy": (None, [vp]),
+        "rs_weights_packed_bytes": (sz, [vp]),
+        "rs_weights_pack": (i, [vp, C.POINTER(_Weights), vp, sz, C.POINTER(_Weights), vp]),
+        "rs_kv_bytes": (sz, [vp, i, i]),
+        "rs_kv_alloc": (i, [vp, i, i, vp, sz, C.POINTER(vp)]),
+        "rs_kv_free": (None, [vp]),
+        "rs_kv_len": (i, [vp, i]),
+        "rs_kv_capacity": (i, [vp]),
+        "rs_kv_reset": (i, [vp]),
+        "rs_kv_truncate": (i, [vp, i, i]),
+        "rs_kv_export": (i, [vp, i, vp, vp, vp]),
+        "rs_kv_import": (i, [vp, i, vp, vp, i, vp]),
+        "rs_workspace_bytes": (sz, [vp, i, i]),
+        "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
+        "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
+        "rs_last_error": (C.c_char_p, []),
+        "rs_version": (i, []),
+        "rs_profile_enable": (i, [vp, i, i]),
+        "rs_profile_read": (i, [vp, C.POINTER(C.c_double), C.POINTER(i)]),
+    }
+    for name, (res, args) in proto.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise RsError(status, load_library().rs_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    if isinstance(stream, int):
+        return stream or None
+    if stream is None:
+        if not torch.cuda.is_available():
+            return None  # GPU-less host: the call can only reach the library's argument checks
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) or None
+
+
+@dataclass
+class LayerConfig:
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    mlp_inter: int
+    rms_eps: float = 1e-6
+    rope_theta: float = 1e6
+    qkv_bias: bool = False
+    max_tokens_per_call: int = 4096
+    max_requests: int = 64
+    max_pos: int = 32768
+
+    def _c(self) -> _Cfg:
+        return _Cfg(self.hidden, self.n_q_heads, self.n_kv_heads, self.head_dim, self.mlp_inter, self.rms_eps,
+                    self.rope_theta, int(self.qkv_bias), self.max_tokens_per_call, self.max_requests, self.max_pos)
+
+
+class PackedWeights:
+    """One layer's weights in the library's packed layout; owns the device slab."""
+
+    def __init__(self, slab, struct: _Weights):
+        self.slab = slab
+        self.struct = struct
+
+
+class KVCache:
+    """One request's KV cache over n_layers layers; owns the device slab and the host handle."""
+
+    def __init__(self, ctx: "Context", handle: int, slab):
+        self.ctx = ctx
+        self.handle = C.c_void_p(handle)
+        self.slab = slab
+
+    def __del__(self):
+        try:
+            if self.handle:
+                load_library().rs_kv_free(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+    def length(self, layer: int = 0) -> int:
+        return load_library().rs_kv_len(self.handle, layer)
+
+    @property
+    def capacity(self) -> int:
+        return load_library().rs_kv_capacity(self.handle)
+
+    def reset(self):
+        _check(load_library().rs_kv_reset(self.handle))
+
+    def truncate(self, layer: int, n_tokens: int):
+        _check(load_library().rs_kv_truncate(self.handle, layer, n_tokens))
+
+    def export(self, layer: int = 0, stream=None):
+        """(K~, V) of `layer` as bf16 tensors [len, Hkv, d] on the device."""
+        import torch
+        n = self.length(layer)
+        cfg = self.ctx.cfg
+        k = torch.empty((n, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        _check(load_library().rs_kv_export(self.handle, layer, _ptr(k) if n else None, _ptr(v) if n else None,
+                                           _stream_handle(stream)))
+        return k, v
+
+    def import_(self, layer: int, k, v, stream=None):
+        """Loads bf16 [n, Hkv, d] device tensors as the cache content of `layer`."""
+        n = int(k.shape[0])
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        _check(load_library().rs_kv_import(self.handle, layer, _ptr(k) if n else None, _ptr(v) if n else None, n,
+                                           _stream_handle(stream)))
+
+
+class Context:
+    def __init__(self, cfg: LayerConfig):
+        self.cfg = cfg
+        self.lib = load_library()
+        h = C.c_void_p()
+        c = cfg._c()
+        _check(self.lib.rs_ctx_create(C.byref(c), C.byref(h)))
+        self.handle = h
+
+    def __del__(self):
+        try:
+            if getattr(self, "handle", None):
+                self.lib.rs_ctx_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+    # ---- sizes
+    def weights_packed_bytes(self) -> int:
+        return self.lib.rs_weights_packed_bytes(self.handle)
+
+    def kv_bytes(self, n_layers: int, capacity: int) -> int:
+        return self.lib.rs_kv_bytes(self.handle, n_layers, capacity)
+
+    def workspace_bytes(self, max_tokens: int, max_requests: int = 1) -> int:
+        return self.lib.rs_workspace_bytes(self.handle, max_tokens, max_requests)
+
+    # ---- allocation helpers (device memory comes from torch)
+    def pack_weights(self, ln1_g, w_qkv, w_o, ln2_g, w_gate_up, w_down, b_qkv=None, stream=None) -> PackedWeights:
+        import torch
+        src = _Weights(_ptr(ln1_g), _ptr(w_qkv), _ptr(b_qkv), _ptr(w_o), _ptr(ln2_g), _ptr(w_gate_up), _ptr(w_down))
+        nbytes = self.weights_packed_bytes()
+        slab = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = _Weights()
+        _check(self.lib.rs_weights_pack(self.handle, C.byref(src), _ptr(slab), nbytes, C.byref(out), _stream_handle(stream)))
+        return PackedWeights(slab, out)
+
+    def kv_alloc(self, n_layers: int, capacity: int) -> KVCache:
+        import torch
+        nbytes = self.kv_bytes(n_layers, capacity)
+        slab = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(self.lib.rs_kv_alloc(self.handle, n_layers, capacity, _ptr(slab), nbytes, C.byref(h)))
+        return KVCache(self, h.value, slab)
+
+    def workspace(self, max_tokens: int, max_requests: int = 1):
+        import torch
+        return torch.empty(self.workspace_bytes(max_tokens, max_requests), dtype=torch.uint8, device="cuda")
+
+    # ---- measurement hook
+    def profile_enable(self, step, max_launches: int = 1024):
+        """step: a name from STEPS, its index, or None / -1 to switch the hook off."""
+        idx = -1 if step is None else (STEPS.index(step) if isinstance(step, str) else int(step))
+        _check(self.lib.rs_profile_enable(self.handle, idx, max_launches))
+
+    def profile_read(self):
+        """(total milliseconds, launches measured) since the hook was enabled or last read."""
+        ms, n = C.c_double(), C.c_int()
+        _check(self.lib.rs_profile_read(self.handle, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+    # ---- the hot path
+    def prefill_chunk(self, packed: PackedWeights, layer: int, kv: KVCache, x, y, workspace, stream=None):
+        """One chunk of one request through one layer; x, y: bf16 [T, H] device tensors (y may be x)."""
+        t = int(x.shape[0])
+        _check(self.lib.rs_prefill_chunk(self.handle, C.byref(packed.struct), layer, kv.handle, _ptr(x), t, _ptr(y),
+                                         _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+        return y
+
+    def prefill_batch(self, packed: PackedWeights, layer: int, kvs: Sequence[KVCache], chunk_lens: Sequence[int],
+                      x, y, workspace, stream=None):
+        """One micro-batch of several requests through one layer; x, y: bf16 [sum chunk_lens, H]."""
+        r = len(kvs)
+        arr_kv = (C.c_void_p * max(r, 1))(*[k.handle.value for k in kvs])
+        arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
+        _check(self.lib.rs_prefill_batch(self.handle, C.byref(packed.struct), layer, arr_kv, arr_len, r, _ptr(x), _ptr(y),
+                                         _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+        return y

@@ -1,0 +1,228 @@
+// Chunk-vs-cache causal GQA attention for gfx950 (flash-style, one pass over the keys, online softmax).
+//
+// Work item = (request, KV head, block of 128 query rows).  The g = Hq/Hkv query heads that share a KV head are
+// stacked into the row dimension: row r of a request's chunk means (token r / g, head r % g), so each K / V tile
+// is fetched once per KV head rather than once per query head.  A 256-thread workgroup (4 wavefronts x 32 query
+// rows) walks the request's cache in tiles of 64 keys.
+//
+// The kernel computes transposed products so that every per-query quantity lives in one lane:
+//   S^T[key, query] = K[key, :] . Q[query, :]      MFMA "A" = K rows from LDS, "B" = Q rows held in registers
+//   O^T[d,   query] = sum_key V^T[d, key] P^T[key, query]    "A" = V^T rows from LDS, "B" = P^T from the S^T registers
+// With v_mfma_f32_32x32x16_bf16 a lane's accumulator column is one query (lane & 31); the two half-waves hold
+// different keys (or different d) of that query.  The running max therefore needs a single cross-half exchange per
+// tile and everything else of the online softmax is lane-local.  The MFMA row -> key assignment swaps two index
+// bits so that the 8 probabilities a lane must feed to one k-step of the second product are 8 consecutive keys
+// sitting in 8 consecutive accumulator registers (no data movement between the two products).
+//
+// Cache layout (private to the library): K is [Hkv][capacity][d]; V is stored transposed in blocks of 64 tokens,
+// [Hkv][capacity/64][d][64], so that a V^T tile is one contiguous 64*d*2-byte run with the key index innermost,
+// which is what the MFMA A operand needs.  Positions >= len inside the last V block hold zeros (the append and
+// import kernels maintain this), so masked probabilities (exact zeros) never meet NaN bit patterns.
+#pragma once
+#include "common.h"
+
+struct ReqDesc {
+    int row0;       // first row of this request in the packed [sum T, ...] activations
+    int T;          // rows this call
+    int P;          // tokens already cached before this call
+    int cap;        // capacity (tokens, multiple of 64) of this request's cache
+    bf16* kcache;   // this layer's K  [Hkv][cap][d]
+    bf16* vtcache;  // this layer's V^T [Hkv][cap/64][d][64]
+};
+
+struct AttnItem {
+    int req;
+    int kvh;
+    int qblock;  // block of 128 stacked query rows
+    int nkb;     // number of 64-key tiles this block must visit
+};
+
+constexpr int ATT_ROWS = 128;  // stacked query rows per workgroup
+constexpr int ATT_KEYS = 64;   // keys per tile
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __restrict__ reqs,
+                                                              const AttnItem* __restrict__ items,
+                                                              const bf16* __restrict__ qkv, int ld_qkv,
+                                                              bf16* __restrict__ out, int ld_out,
+                                                              int g, float scale_log2e) {
+    constexpr int KSTEPS = D / 16;          // k-steps of the S^T product
+    constexpr int DT = D / 32;              // 32-row tiles of O^T
+    constexpr int K_ROW_BYTES = D * 2;
+    constexpr int K_CPR = K_ROW_BYTES / 16; // 16-byte chunks per K row: 16 (d=128) or 8 (d=64)
+    constexpr int TILE_BYTES = ATT_KEYS * D * 2;
+    constexpr int LOADS = TILE_BYTES / (256 * 16);  // 16-byte loads per thread per tile: 4 or 2
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile | V^T tile]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    const AttnItem item = items[blockIdx.x];
+    const ReqDesc rq = reqs[item.req];
+    const int cap = rq.cap;
+    const int rows_total = rq.T * g;
+    const int row = item.qblock * ATT_ROWS + wave * 32 + l32;
+    const int row_c = min(row, rows_total - 1);
+    const int tok = row_c / g;
+    const int head = item.kvh * g + (row_c - tok * g);
+    const int qpos = rq.P + tok;
+    // wave-uniform visibility bounds
+    const int wrow_lo = min(item.qblock * ATT_ROWS + wave * 32, rows_total - 1);
+    const int wrow_hi = min(item.qblock * ATT_ROWS + wave * 32 + 31, rows_total - 1);
+    const int wpos_lo = rq.P + wrow_lo / g;
+    const int wpos_hi = rq.P + wrow_hi / g;
+
+    // ---- Q fragments: 8 consecutive d values per lane per k-step
+    bf16x8 qf[KSTEPS];
+    {
+        const bf16* qp = qkv + (size_t)(rq.row0 + tok) * ld_qkv + head * D + half * 8;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+    }
+
+    // ---- tile loader: both tiles are contiguous TILE_BYTES runs in the cache
+    const char* ksrc = reinterpret_cast<const char*>(rq.kcache + (size_t)item.kvh * cap * D);
+    const char* vsrc = reinterpret_cast<const char*>(rq.vtcache + (size_t)item.kvh * (cap / ATT_KEYS) * D * ATT_KEYS);
+    uint32_t k_src_off[LOADS], v_src_off[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int q = i * 256 + tid;  // destination 16-byte slot in LDS
+        {
+            const int r = q / K_CPR, p = q % K_CPR;
+            const int c = (K_CPR == 16) ? (p ^ (r & 15)) : (p ^ ((r >> 1) & 7));
+            k_src_off[i] = (uint32_t)(r * K_ROW_BYTES + c * 16);
+        }
+        {
+            const int r = q >> 3, p = q & 7;
+            const int c = p ^ ((r >> 1) & 7);
+            v_src_off[i] = (uint32_t)(r * 128 + c * 16);
+        }
+    }
+    uint4 rk[LOADS], rv[LOADS];
+    auto load_tile = [&](int kb) {
+        const size_t tb = (size_t)kb * TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) rk[i] = ld_global_16(ksrc + tb + k_src_off[i]);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) rv[i] = ld_global_16(vsrc + tb + v_src_off[i]);
+    };
+    auto park_tile = [&](int buf) {
+        char* ks = smem + buf * (2 * TILE_BYTES);
+        char* vs = ks + TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) *reinterpret_cast<uint4*>(ks + (i * 256 + tid) * 16) = rk[i];
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) *reinterpret_cast<uint4*>(vs + (i * 256 + tid) * 16) = rv[i];
+    };
+
+    // ---- fragment read geometry
+    // S^T product: MFMA row rho = l32 reads key pi(rho) = rho with bits 2 and 3 swapped
+    const int pi = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    uint32_t k_row_off[2], k_swz[2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+        const int r = mi * 32 + pi;
+        k_row_off[mi] = (uint32_t)(r * K_ROW_BYTES);
+        k_swz[mi] = (K_CPR == 16) ? (uint32_t)(r & 15) : (uint32_t)((r >> 1) & 7);
+    }
+    const uint32_t v_swz = (uint32_t)((lane >> 1) & 7);
+
+    f32x16 acc_o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.0f;
+    float m_run = -INFINITY;  // running max of the raw scores of this lane's query (shared by both half-waves)
+    float l_run = 0.0f;       // running sum over THIS half-wave's keys
+
+    const int nkb = item.nkb;
+    load_tile(0);
+    park_tile(0);
+    __syncthreads();
+
+    for (int kb = 0; kb < nkb; ++kb) {
+        const int buf = kb & 1;
+        const bool more = (kb + 1) < nkb;
+        if (more) load_tile(kb + 1);
+        const int key0 = kb * ATT_KEYS;
+        if (key0 <= wpos_hi) {  // some query of this wavefront sees some key of the tile
+            const char* ks = smem + buf * (2 * TILE_BYTES);
+            const char* vs = ks + TILE_BYTES;
+            f32x16 s[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[mi][r] = 0.0f;
+#pragma unroll
+                for (int kk = 0; kk < KSTEPS; ++kk) {
+                    const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
+                    bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_row_off[mi] + c);
+                    s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mi], 0, 0, 0);
+                }
+            }
+            // register r of s[mi] holds key  key0 + mi*32 + 16*(r>>3) + 8*half + (r&7)
+            if (key0 + ATT_KEYS - 1 > wpos_lo) {  // tile straddles the causal boundary of some query here
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + mi * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+                        s[mi][r] = (key <= qpos) ? s[mi][r] : -INFINITY;
+                    }
+            }
+            float mloc = s[0][0];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[mi][r]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, WAVE));
+            const float m_new = fmaxf(m_run, mloc);          // finite: key 0 is visible to every query
+            const float alpha = exp2f((m_run - m_new) * scale_log2e);
+            const float mb = m_new * scale_log2e;
+            m_run = m_new;
+            float psum = 0.0f;
+            bf16x8 pf[4];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = exp2f(s[mi][r] * scale_log2e - mb);
+                    psum += p;
+                    pf[mi * 2 + (r >> 3)][r & 7] = f32_to_bf16(p);
+                }
+            l_run = l_run * alpha + psum;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                const uint32_t vrow = (uint32_t)(t * 32 + l32) * 128u;
+#pragma unroll
+                for (int ksx = 0; ksx < 4; ++ksx) {
+                    const uint32_t c = ((uint32_t)(ksx * 2 + half) ^ v_swz) * 16u;
+                    bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + vrow + c);
+                    acc_o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ksx], acc_o[t], 0, 0, 0);
+                }
+            }
+        }
+        if (more) park_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store.  acc_o[t][r]: d = t*32 + 8*(r>>2) + 4*half + (r&3), query = this lane's row
+    const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
+    if (row < rows_total) {
+        const float inv = 1.0f / l_tot;
+        bf16* op = out + (size_t)(rq.row0 + tok) * ld_out + head * D + 4 * half;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc_o[t][4 * q + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + t * 32 + 8 * q) = o;
+            }
+    }
+}

@@ -1,0 +1,222 @@
+// bf16 MFMA GEMM for gfx950:  out[M,N] = epilogue( X[M,K] * W[N,K]^T ),  fp32 accumulation.
+//
+// Both operands are K-contiguous ("NT" form), which is what v_mfma_f32_32x32x16_bf16 wants: each lane
+// feeds 8 consecutive k values of one row.  A 256x256 output tile is owned by one 256-thread workgroup
+// (4 wavefronts in a 2x2 grid, 128x128 per wavefront = 4x4 MFMA tiles of 32x32, 256 fp32 accumulators
+// per lane).  The weight rows ride on the MFMA "A" side and the token rows on the "B" side, so a lane ends
+// up holding one token and runs of 4 consecutive output features: the epilogue (bias, residual, SwiGLU)
+// is lane-local and stores 8-byte bf16 groups.
+//
+// K is walked in slabs of 64.  A slab of either operand is 256 rows x 128 bytes; it is kept in LDS as
+// 16-byte chunks with the chunk index XOR-ed by ((row >> 1) & 7), which makes both the linear 16-byte
+// stores of the loader and the row-strided 16-byte fragment reads of the MFMA feed bank-conflict free.
+// LDS is double buffered (2 x 64 KB of the CU's 160 KB); the next slab travels global -> registers while
+// the current one is multiplied, and is parked in the other LDS buffer before the single barrier per slab.
+//
+// Workgroup ids are dispatched round-robin over the 8 XCDs; the kernel re-maps them so that each XCD owns a
+// contiguous range of tile columns (all row tiles of a weight column block run on one XCD, close in time),
+// which makes the weight stream single-pass through HBM and lets the XCD's L2 serve the activation re-reads.
+#pragma once
+#include "common.h"
+
+enum GemmEpilogue {
+    EPI_BIAS = 0,      // out = bf16(acc + bias[n])          (bias may be null)
+    EPI_RESIDUAL = 1,  // out = bf16(acc + resid[m, n])
+    EPI_SWIGLU = 2,    // W rows interleaved in 32-row blocks (gate, up, gate, up, ...): out[m, n/2] = bf16(silu(gate) * up)
+    EPI_PARTIAL = 3    // split-K: fp32 partial sums to partial[split][m][n]
+};
+
+struct GemmArgs {
+    const bf16* X;      // [M, K] activations, row stride ldx elements
+    const bf16* W;      // [N, K] weights, row stride K
+    bf16* out;          // [M, ldo]
+    const bf16* bias;   // [N] or null
+    const bf16* resid;  // [M, ldr]
+    float* partial;     // [splits, M, N]
+    int ldx, ldo, ldr;
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int k_slabs_per_split;  // K/64 slabs handled by one blockIdx.y
+};
+
+constexpr int GEMM_BM = 256, GEMM_BN = 256, GEMM_BK = 64;
+constexpr int GEMM_STAGE_BYTES = GEMM_BM * GEMM_BK * 2;          // one operand, one slab: 32 KB
+constexpr int GEMM_LDS_BYTES = 4 * GEMM_STAGE_BYTES;             // 2 operands x 2 buffers
+
+RS_DEVICE float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wn = wave & 1;   // which 128-wide half of the tile's features
+    const int wm = wave >> 1;  // which 128-row half of the tile's tokens
+    const int half = lane >> 5;
+    const int l32 = lane & 31;
+
+    // ---- XCD-aware tile assignment
+    const int nwg = a.tiles_m * a.tiles_n;
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, loc = pid >> 3;
+    const int base = nwg >> 3, rem = nwg & 7;
+    const int logical = (xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base) + loc;
+    const int tm = logical % a.tiles_m;
+    const int tn = logical / a.tiles_m;
+    const int m0 = tm * GEMM_BM;
+    const int n0 = tn * GEMM_BN;
+
+    const int split = blockIdx.y;
+    const int slabs_total = a.K / GEMM_BK;
+    const int s0 = split * a.k_slabs_per_split;
+    const int s1 = min(s0 + a.k_slabs_per_split, slabs_total);
+
+    // ---- loader geometry: thread -> (row within a 32-row group, 16-byte chunk of the 128-byte slab row)
+    const int ld_row = tid >> 3;
+    const int ld_chunk = (tid & 7) ^ ((tid >> 4) & 7);
+    uint32_t x_off[8];  // byte offsets of this thread's 8 rows of X (rows past M are clamped: loaded, never stored)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int r = min(m0 + i * 32 + ld_row, a.M - 1);
+        x_off[i] = (uint32_t)r * (uint32_t)a.ldx * 2u + (uint32_t)ld_chunk * 16u;
+    }
+    const uint32_t w_off0 = (uint32_t)(n0 + ld_row) * (uint32_t)a.K * 2u + (uint32_t)ld_chunk * 16u;
+    const uint32_t w_step = 32u * (uint32_t)a.K * 2u;
+    const char* Xb = reinterpret_cast<const char*>(a.X);
+    const char* Wb = reinterpret_cast<const char*>(a.W);
+
+    // ---- fragment read geometry
+    const int swz = (lane >> 1) & 7;
+    uint32_t fr_w[4], fr_x[4];  // LDS byte offset of the lane's row in each 32-row MFMA tile (chunk added per k-step)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        fr_w[t] = (uint32_t)(wn * 128 + t * 32 + l32) * 128u;
+        fr_x[t] = (uint32_t)(wm * 128 + t * 32 + l32) * 128u;
+    }
+
+    f32x16 acc[4][4];  // [feature tile][token tile]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    uint4 rx[8], rw[8];
+    auto load_slab = [&](int s) {
+        const uint32_t kb = (uint32_t)s * (GEMM_BK * 2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rx[i] = ld_global_16(Xb + (x_off[i] + kb));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rw[i] = ld_global_16(Wb + (w_off0 + (uint32_t)i * w_step + kb));
+    };
+    auto park_slab = [&](int buf) {
+        char* xs = smem + buf * (2 * GEMM_STAGE_BYTES);
+        char* ws = xs + GEMM_STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(xs + i * 4096 + tid * 16) = rx[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(ws + i * 4096 + tid * 16) = rw[i];
+    };
+
+    if (s0 < s1) {
+        load_slab(s0);
+        park_slab(0);
+    }
+    __syncthreads();
+
+    for (int s = s0; s < s1; ++s) {
+        const int buf = (s - s0) & 1;
+        const bool more = (s + 1) < s1;
+        if (more) load_slab(s + 1);
+        const char* xs = smem + buf * (2 * GEMM_STAGE_BYTES);
+        const char* ws = xs + GEMM_STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const uint32_t coff = (uint32_t)(((kk * 2 + half) ^ swz) * 16);
+            bf16x8 wf[4], xf[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) wf[t] = *reinterpret_cast<const bf16x8*>(ws + fr_w[t] + coff);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xf[t] = *reinterpret_cast<const bf16x8*>(xs + fr_x[t] + coff);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) park_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][r]: token m = m0 + wm*128 + j*32 + l32,
+    //      feature n = n0 + wn*128 + i*32 + 8*(r>>2) + 4*half + (r&3).
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 128 + j * 32 + l32;
+        if (m >= a.M) continue;
+        if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = (n0 + wn * 128) / 2 + i2 * 32 + 8 * q + 4 * half;
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = f32_to_bf16(silu_f32(acc[2 * i2][j][4 * q + e]) * acc[2 * i2 + 1][j][4 * q + e]);
+                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + col) = o;
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * 128 + i * 32 + 8 * q + 4 * half;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+                    if constexpr (EPI == EPI_PARTIAL) {
+                        f32x4 o = {v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4*>(a.partial + ((size_t)split * a.M + m) * a.N + n) = o;
+                    } else {
+                        if constexpr (EPI == EPI_BIAS) {
+                            if (a.bias != nullptr) {
+                                bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(b[e]);
+                            }
+                        } else {
+                            bf16x4 r4 = *reinterpret_cast<const bf16x4*>(a.resid + (size_t)m * a.ldr + n);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(r4[e]);
+                        }
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e]);
+                        *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + n) = o;
+                    }
+                }
+        }
+    }
+}
+
+// Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).
+__global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float* __restrict__ partial, int splits,
+                                                                     const bf16* __restrict__ resid, int ldr,
+                                                                     bf16* __restrict__ out, int ldo, int M, int N) {
+    const size_t quads = (size_t)M * (N / 4);
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(q / (N / 4));
+        const int n = (int)(q % (N / 4)) * 4;
+        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(resid + (size_t)m * ldr + n);
+        float v[4] = {bf16_to_f32(r4[0]), bf16_to_f32(r4[1]), bf16_to_f32(r4[2]), bf16_to_f32(r4[3])};
+        for (int s = 0; s < splits; ++s) {
+            f32x4 p = *reinterpret_cast<const f32x4*>(partial + ((size_t)s * M + m) * N + n);
+            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+        }
+        bf16x4 o = {f32_to_bf16(v[0]), f32_to_bf16(v[1]), f32_to_bf16(v[2]), f32_to_bf16(v[3])};
+        *reinterpret_cast<bf16x4*>(out + (size_t)m * ldo + n) = o;
+    }
+}

@@ -1,0 +1,638 @@
+// Host side of the C ABI declared in include/rserve_prefill.h: argument checks, per-call descriptors and the
+// kernel sequence of one decoder layer over one chunk / micro-batch.  All device work goes to the caller's stream.
+#include "../../include/rserve_prefill.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "attention.h"
+#include "common.h"
+#include "elementwise.h"
+#include "gemm_bf16.h"
+
+namespace {
+
+thread_local std::string g_last_error = "";
+
+rs_status fail(rs_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return st;
+}
+
+#define RS_HIP(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) return fail(RS_EHIP, "%s: %s", #expr, hipGetErrorString(e_));       \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+constexpr int RING_SLOTS = 32;
+
+}  // namespace
+
+struct rs_ctx {
+    rs_layer_cfg cfg;
+    int qkv_dim, q_dim, kv_dim, group;
+    float2* rope_dev = nullptr;  // [max_pos][d/2] (cos, sin)
+    // pinned staging ring for per-call descriptors
+    char* pinned[RING_SLOTS] = {};
+    hipEvent_t slot_done[RING_SLOTS] = {};
+    bool slot_used[RING_SLOTS] = {};
+    size_t slot_bytes = 0;
+    int next_slot = 0;
+    int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
+    bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
+    // measurement hook: HIP events around every launch of one step of the layer
+    int prof_step = -1;
+    int prof_count = 0;
+    std::vector<hipEvent_t> prof_events;  // (start, stop) pairs
+};
+
+struct rs_kv {
+    rs_ctx* ctx;
+    int n_layers;
+    int cap;  // multiple of 64
+    char* base;
+    size_t k_bytes;      // one layer's K
+    size_t layer_bytes;  // K + V^T
+    std::vector<int> len;
+    bf16* k_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes); }
+    bf16* vt_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes + k_bytes); }
+};
+
+namespace {
+
+struct DescSizes {
+    size_t reqs, items, vblocks, total;
+};
+
+DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
+    DescSizes d;
+    const size_t n_items = ((size_t)(max_tokens * (size_t)c->group + ATT_ROWS - 1) / ATT_ROWS + max_requests) * c->cfg.n_kv_heads;
+    const size_t n_vb = (size_t)max_tokens / 64 + 2 * (size_t)max_requests + 1;
+    d.reqs = align_up(sizeof(ReqDesc) * std::max(max_requests, 1), 256);
+    d.items = align_up(sizeof(AttnItem) * n_items, 256);
+    d.vblocks = align_up(sizeof(VBlockItem) * n_vb, 256);
+    d.total = d.reqs + d.items + d.vblocks;
+    return d;
+}
+
+int choose_splitk(const rs_ctx* c, int tiles, int k_slabs) {
+    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_slabs));
+    // one 256x256 tile per CU: split K when less than ~60% of the 256 CUs would have a tile
+    int s = 1;
+    while (s < 4 && tiles * (s + 1) <= 256 && k_slabs / (s + 1) >= 8) ++s;
+    return s;
+}
+
+struct WorkspaceLayout {
+    size_t h, qkv, attn, r, act, partial, desc, total;
+};
+
+WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
+    const rs_layer_cfg& f = c->cfg;
+    WorkspaceLayout w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes, 256);
+        return o;
+    };
+    const size_t t = (size_t)std::max(T, 1);
+    w.h = take(t * f.hidden * 2);
+    w.qkv = take(t * c->qkv_dim * 2);
+    w.attn = take(t * c->q_dim * 2);
+    w.r = take(t * f.hidden * 2);
+    w.act = take(t * f.mlp_inter * 2);
+    w.partial = take(4 * t * f.hidden * 4);  // up to 4 split-K partial planes of [T, H] fp32
+    w.desc = take(desc_sizes(c, T, R).total);
+    w.total = off;
+    return w;
+}
+
+template <int EPI>
+rs_status launch_gemm(GemmArgs a, int splits, hipStream_t st) {
+    a.tiles_m = (a.M + GEMM_BM - 1) / GEMM_BM;
+    a.tiles_n = a.N / GEMM_BN;
+    const int slabs = a.K / GEMM_BK;
+    a.k_slabs_per_split = (slabs + splits - 1) / splits;
+    dim3 grid(a.tiles_m * a.tiles_n, splits);
+    hipLaunchKernelGGL(gemm_bf16_256x256_kernel<EPI>, grid, dim3(256), GEMM_LDS_BYTES, st, a);
+    RS_HIP(hipGetLastError());
+    return RS_OK;
+}
+
+// out = resid + X W^T, through split-K partials when that fills the machine better.
+rs_status gemm_residual(const rs_ctx* c, const bf16* X, int ldx, const bf16* W, const bf16* resid, bf16* out,
+                        int M, int N, int K, float* partial, hipStream_t st) {
+    GemmArgs a{};
+    a.X = X; a.ldx = ldx; a.W = W; a.out = out; a.ldo = N; a.resid = resid; a.ldr = N; a.partial = partial;
+    a.M = M; a.N = N; a.K = K;
+    const int tiles = ((M + GEMM_BM - 1) / GEMM_BM) * (N / GEMM_BN);
+    const int splits = choose_splitk(c, tiles, K / GEMM_BK);
+    if (splits == 1) return launch_gemm<EPI_RESIDUAL>(a, 1, st);
+    rs_status s = launch_gemm<EPI_PARTIAL>(a, splits, st);
+    if (s != RS_OK) return s;
+    const size_t quads = (size_t)M * (N / 4);
+    const int blocks = (int)std::min<size_t>((quads + 255) / 256, 256 * 8);
+    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3(blocks), dim3(256), 0, st, partial, splits, resid, N, out, N, M, N);
+    RS_HIP(hipGetLastError());
+    return RS_OK;
+}
+
+// Brackets one step of the layer with HIP events on the call's stream when that step is being measured.
+struct StepTimer {
+    rs_ctx* c;
+    hipStream_t st;
+    bool on(int step) const { return c->prof_step == step && 2 * (c->prof_count + 1) <= (int)c->prof_events.size(); }
+    void begin(int step) const {
+        if (on(step)) (void)hipEventRecord(c->prof_events[2 * c->prof_count], st);
+    }
+    void end(int step) const {
+        if (on(step)) {
+            (void)hipEventRecord(c->prof_events[2 * c->prof_count + 1], st);
+            ++c->prof_count;
+        }
+    }
+};
+
+template <int D>
+rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs, int n_reqs,
+                                const AttnItem* d_items, int n_items, const VBlockItem* d_vb, int n_vb,
+                                int T, hipStream_t st, const StepTimer& tm) {
+    const rs_layer_cfg& f = c->cfg;
+    tm.begin(RS_STEP_ROPE_APPEND_K);
+    hipLaunchKernelGGL(rope_append_k_kernel<D>, dim3(T), dim3(256), 0, st, qkv, c->qkv_dim, d_reqs, n_reqs,
+                       (const float2*)c->rope_dev, f.n_q_heads, f.n_kv_heads);
+    RS_HIP(hipGetLastError());
+    tm.end(RS_STEP_ROPE_APPEND_K);
+    tm.begin(RS_STEP_APPEND_V);
+    hipLaunchKernelGGL(append_v_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
+                       d_reqs, d_vb, f.n_q_heads, f.n_kv_heads);
+    RS_HIP(hipGetLastError());
+    tm.end(RS_STEP_APPEND_V);
+    const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
+    tm.begin(RS_STEP_ATTENTION);
+    hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
+                       (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+    RS_HIP(hipGetLastError());
+    tm.end(RS_STEP_ATTENTION);
+    return RS_OK;
+}
+
+rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
+                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return fail(RS_EINVAL, "ctx is null");
+    if (!w) return fail(RS_EINVAL, "weights are null");
+    const rs_layer_cfg& f = ctx->cfg;
+    if (!w->ln1_g || !w->w_qkv || !w->w_o || !w->ln2_g || !w->w_gate_up || !w->w_down)
+        return fail(RS_EINVAL, "a weight pointer is null");
+    if (f.qkv_bias && !w->b_qkv) return fail(RS_EINVAL, "cfg.qkv_bias is set but b_qkv is null");
+    if (R < 0) return fail(RS_EINVAL, "R = %d is negative", R);
+    if (R > f.max_requests) return fail(RS_EINVAL, "R = %d exceeds max_requests = %d", R, f.max_requests);
+    if (R > 0 && (!kvs || !lens)) return fail(RS_EINVAL, "kvs / chunk_lens is null");
+    long total = 0;
+    for (int i = 0; i < R; ++i) {
+        if (!kvs[i]) return fail(RS_EINVAL, "kvs[%d] is null", i);
+        if (kvs[i]->ctx != ctx) return fail(RS_ESTATE, "kvs[%d] belongs to another context", i);
+        if (layer < 0 || layer >= kvs[i]->n_layers) return fail(RS_EINVAL, "layer %d out of range for kvs[%d]", layer, i);
+        if (lens[i] < 0) return fail(RS_EINVAL, "chunk_lens[%d] = %d is negative", i, lens[i]);
+        total += lens[i];
+    }
+    if (total > f.max_tokens_per_call)
+        return fail(RS_EINVAL, "%ld rows exceed max_tokens_per_call = %d", total, f.max_tokens_per_call);
+    {
+        std::vector<const rs_kv*> sorted(kvs, kvs + R);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())
+            return fail(RS_EINVAL, "the same rs_kv appears twice in one micro-batch");
+    }
+    for (int i = 0; i < R; ++i) {
+        const long after = (long)kvs[i]->len[layer] + lens[i];
+        if (after > kvs[i]->cap)
+            return fail(RS_ECAPACITY, "request %d: %ld tokens exceed cache capacity %d", i, after, kvs[i]->cap);
+        if (after > f.max_pos) return fail(RS_ECAPACITY, "request %d: %ld tokens exceed max_pos %d", i, after, f.max_pos);
+    }
+    if (total == 0) return RS_OK;
+    const int T = (int)total;
+    if (!x || !y) return fail(RS_EINVAL, "x / y is null");
+    if (!aligned(x, 16) || !aligned(y, 16)) return fail(RS_EINVAL, "x / y must be 16-byte aligned");
+    if (!ws) return fail(RS_EINVAL, "workspace is null");
+    if (!aligned(ws, 256)) return fail(RS_EINVAL, "workspace must be 256-byte aligned");
+    const WorkspaceLayout L = ws_layout(ctx, T, R);
+    if (ws_bytes < L.total) return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, L.total);
+    if (!ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
+
+    // ---- host descriptors
+    std::vector<ReqDesc> reqs;
+    std::vector<AttnItem> items;
+    std::vector<VBlockItem> vbs;
+    const int g = ctx->group;
+    int row0 = 0;
+    for (int i = 0; i < R; ++i) {
+        const int Ti = lens[i];
+        if (Ti == 0) continue;
+        rs_kv* kv = kvs[i];
+        const int P = kv->len[layer];
+        ReqDesc d;
+        d.row0 = row0; d.T = Ti; d.P = P; d.cap = kv->cap;
+        d.kcache = kv->k_of(layer);
+        d.vtcache = kv->vt_of(layer);
+        const int ri = (int)reqs.size();
+        reqs.push_back(d);
+        const int nqb = (Ti * g + ATT_ROWS - 1) / ATT_ROWS;
+        for (int qb = 0; qb < nqb; ++qb) {
+            const int t_max = std::min(Ti - 1, (qb * ATT_ROWS + ATT_ROWS - 1) / g);
+            const int nkb = (P + t_max + 1 + ATT_KEYS - 1) / ATT_KEYS;
+            for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb});
+        }
+        for (int b = P / 64; b <= (P + Ti - 1) / 64; ++b) vbs.push_back(VBlockItem{ri, b});
+        row0 += Ti;
+    }
+    // heaviest work first: the tail of the launch is then made of short items
+    std::stable_sort(items.begin(), items.end(), [](const AttnItem& a, const AttnItem& b) { return a.nkb > b.nkb; });
+
+    const DescSizes ds = desc_sizes(ctx, T, R);
+    if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
+        sizeof(VBlockItem) * vbs.size() > ds.vblocks || ds.total > ctx->slot_bytes)
+        return fail(RS_EINVAL, "internal: descriptor sizing");
+
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int slot = ctx->next_slot;
+    if (ctx->slot_used[slot]) RS_HIP(hipEventSynchronize(ctx->slot_done[slot]));
+    char* stage = ctx->pinned[slot];
+    memcpy(stage, reqs.data(), sizeof(ReqDesc) * reqs.size());
+    memcpy(stage + ds.reqs, items.data(), sizeof(AttnItem) * items.size());
+    memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(VBlockItem) * vbs.size());
+    char* wsb = reinterpret_cast<char*>(ws);
+    RS_HIP(hipMemcpyAsync(wsb + L.desc, stage, ds.total, hipMemcpyHostToDevice, st));
+    RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
+    ctx->slot_used[slot] = true;
+    ctx->next_slot = (slot + 1) % RING_SLOTS;
+    const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
+    const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
+    const VBlockItem* d_vb = reinterpret_cast<const VBlockItem*>(wsb + L.desc + ds.reqs + ds.items);
+
+    bf16* h = reinterpret_cast<bf16*>(wsb + L.h);
+    bf16* qkv = reinterpret_cast<bf16*>(wsb + L.qkv);
+    bf16* attn = reinterpret_cast<bf16*>(wsb + L.attn);
+    bf16* r = reinterpret_cast<bf16*>(wsb + L.r);
+    bf16* act = reinterpret_cast<bf16*>(wsb + L.act);
+    float* partial = reinterpret_cast<float*>(wsb + L.partial);
+    const bf16* xb = reinterpret_cast<const bf16*>(x);
+    bf16* yb = reinterpret_cast<bf16*>(y);
+    const int H = f.hidden, I = f.mlp_inter;
+    rs_status s;
+    const StepTimer tm{ctx, st};
+
+    // h = rmsnorm(x; g1)
+    tm.begin(RS_STEP_RMSNORM_1);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, st, xb, (const bf16*)w->ln1_g, h, T, H, f.rms_eps);
+    RS_HIP(hipGetLastError());
+    tm.end(RS_STEP_RMSNORM_1);
+    // qkv = h Wqkv^T (+ b)
+    tm.begin(RS_STEP_QKV_GEMM);
+    {
+        GemmArgs a{};
+        a.X = h; a.ldx = H; a.W = (const bf16*)w->w_qkv; a.out = qkv; a.ldo = ctx->qkv_dim;
+        a.bias = f.qkv_bias ? (const bf16*)w->b_qkv : nullptr;
+        a.M = T; a.N = ctx->qkv_dim; a.K = H;
+        if ((s = launch_gemm<EPI_BIAS>(a, 1, st)) != RS_OK) return s;
+    }
+    tm.end(RS_STEP_QKV_GEMM);
+    // RoPE, cache append, attention
+    if (f.head_dim == 128)
+        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, (int)reqs.size(), d_items, (int)items.size(), d_vb, (int)vbs.size(), T, st, tm);
+    else
+        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, (int)reqs.size(), d_items, (int)items.size(), d_vb, (int)vbs.size(), T, st, tm);
+    if (s != RS_OK) return s;
+    // r = x + attn Wo^T
+    tm.begin(RS_STEP_O_GEMM);
+    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, st)) != RS_OK) return s;
+    tm.end(RS_STEP_O_GEMM);
+    // h2 = rmsnorm(r; g2)
+    tm.begin(RS_STEP_RMSNORM_2);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16*)r, (const bf16*)w->ln2_g, h, T, H, f.rms_eps);
+    RS_HIP(hipGetLastError());
+    tm.end(RS_STEP_RMSNORM_2);
+    // act = silu(h2 Wg^T) * (h2 Wu^T)
+    tm.begin(RS_STEP_GATE_UP_GEMM);
+    {
+        GemmArgs a{};
+        a.X = h; a.ldx = H; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I;
+        a.M = T; a.N = 2 * I; a.K = H;
+        if ((s = launch_gemm<EPI_SWIGLU>(a, 1, st)) != RS_OK) return s;
+    }
+    tm.end(RS_STEP_GATE_UP_GEMM);
+    // y = r + act Wd^T
+    tm.begin(RS_STEP_DOWN_GEMM);
+    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, st)) != RS_OK) return s;
+    tm.end(RS_STEP_DOWN_GEMM);
+
+    for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
+    return RS_OK;
+}
+
+}  // namespace
+
+// =============================================================================================== C ABI
+extern "C" {
+
+const char* rs_last_error(void) { return g_last_error.c_str(); }
+int rs_version(void) { return 1; }
+
+rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
+    if (!cfg || !out) return fail(RS_EINVAL, "cfg / out is null");
+    *out = nullptr;
+    const rs_layer_cfg& f = *cfg;
+    if (f.hidden <= 0 || f.n_q_heads <= 0 || f.n_kv_heads <= 0 || f.mlp_inter <= 0 || f.max_tokens_per_call <= 0 ||
+        f.max_requests <= 0 || f.max_pos <= 0)
+        return fail(RS_EINVAL, "sizes must be positive");
+    if (f.head_dim != 64 && f.head_dim != 128) return fail(RS_EINVAL, "head_dim must be 64 or 128");
+    if (f.n_q_heads % f.n_kv_heads) return fail(RS_EINVAL, "n_kv_heads must divide n_q_heads");
+    const int q_dim = f.n_q_heads * f.head_dim, kv_dim = f.n_kv_heads * f.head_dim, qkv_dim = q_dim + 2 * kv_dim;
+    if (f.hidden % 256) return fail(RS_EINVAL, "hidden must be a multiple of 256");
+    if (qkv_dim % 256) return fail(RS_EINVAL, "(Hq + 2 Hkv) * head_dim must be a multiple of 256");
+    if (f.mlp_inter % 128) return fail(RS_EINVAL, "mlp_inter must be a multiple of 128");
+    if (!(f.rms_eps >= 0.0f) || !(f.rope_theta > 0.0f)) return fail(RS_EINVAL, "rms_eps / rope_theta out of range");
+    if ((size_t)f.max_tokens_per_call * (size_t)std::max(qkv_dim, f.mlp_inter) * 2 >= (size_t)1 << 31)
+        return fail(RS_EINVAL, "max_tokens_per_call too large for 32-bit row offsets");
+    if ((size_t)std::max(2 * f.mlp_inter, qkv_dim) * (size_t)f.hidden * 2 >= (size_t)1 << 31 ||
+        (size_t)f.hidden * (size_t)f.mlp_inter * 2 >= (size_t)1 << 31)
+        return fail(RS_EINVAL, "weight matrix too large for 32-bit row offsets");
+
+    rs_ctx* c = new rs_ctx();
+    c->cfg = f;
+    c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
+    if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
+    auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
+
+    c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) {
+        (void)hipGetLastError();
+        *out = c;  // host-only context: every check that precedes a launch still works
+        return RS_OK;
+    }
+    c->has_device = true;
+
+    // RoPE table from fp64 angles
+    const int half = f.head_dim / 2;
+    std::vector<float2> table((size_t)f.max_pos * half);
+    std::vector<double> inv_freq(half);
+    for (int j = 0; j < half; ++j) inv_freq[j] = std::pow((double)f.rope_theta, -2.0 * j / f.head_dim);
+    for (int p = 0; p < f.max_pos; ++p)
+        for (int j = 0; j < half; ++j) {
+            const double ang = (double)p * inv_freq[j];
+            table[(size_t)p * half + j] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+        }
+    hipError_t e = hipMalloc((void**)&c->rope_dev, table.size() * sizeof(float2));
+    if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipMalloc(rope table): %s", hipGetErrorString(e)));
+    e = hipMemcpy(c->rope_dev, table.data(), table.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipMemcpy(rope table): %s", hipGetErrorString(e)));
+
+    for (int i = 0; i < RING_SLOTS; ++i) {
+        e = hipHostMalloc((void**)&c->pinned[i], c->slot_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipHostMalloc: %s", hipGetErrorString(e)));
+        e = hipEventCreateWithFlags(&c->slot_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
+    }
+    // kernels that use more than 64 KB of LDS must opt in
+    e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_BIAS>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
+    if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
+    *out = c;
+    return RS_OK;
+}
+
+void rs_ctx_destroy(rs_ctx* c) {
+    if (!c) return;
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    if (c->rope_dev) (void)hipFree(c->rope_dev);
+    for (int i = 0; i < RING_SLOTS; ++i) {
+        if (c->slot_done[i]) (void)hipEventDestroy(c->slot_done[i]);
+        if (c->pinned[i]) (void)hipHostFree(c->pinned[i]);
+    }
+    delete c;
+}
+
+size_t rs_weights_packed_bytes(const rs_ctx* c) {
+    if (!c) return 0;
+    const rs_layer_cfg& f = c->cfg;
+    const size_t H = f.hidden, I = f.mlp_inter;
+    size_t b = 0;
+    b += align_up(H * 2, 256) * 2;                    // gains
+    b += align_up((size_t)c->qkv_dim * H * 2, 256);   // w_qkv
+    b += align_up((size_t)c->qkv_dim * 2, 256);       // b_qkv
+    b += align_up(H * c->q_dim * 2, 256);             // w_o
+    b += align_up(2 * I * H * 2, 256);                // w_gate_up
+    b += align_up(H * I * 2, 256);                    // w_down
+    return b;
+}
+
+rs_status rs_weights_pack(rs_ctx* c, const rs_layer_weights* src, void* dst, size_t dst_bytes, rs_layer_weights* packed,
+                          void* stream) {
+    if (!c || !src || !dst || !packed) return fail(RS_EINVAL, "null argument");
+    const rs_layer_cfg& f = c->cfg;
+    if (!src->ln1_g || !src->w_qkv || !src->w_o || !src->ln2_g || !src->w_gate_up || !src->w_down)
+        return fail(RS_EINVAL, "a source weight pointer is null");
+    if (f.qkv_bias && !src->b_qkv) return fail(RS_EINVAL, "cfg.qkv_bias is set but b_qkv is null");
+    if (!aligned(dst, 256)) return fail(RS_EINVAL, "dst must be 256-byte aligned");
+    if (!aligned(src->w_gate_up, 16)) return fail(RS_EINVAL, "w_gate_up must be 16-byte aligned");
+    if (dst_bytes < rs_weights_packed_bytes(c)) return fail(RS_EWORKSPACE, "dst has %zu bytes, need %zu", dst_bytes, rs_weights_packed_bytes(c));
+    if (!c->has_device) return fail(RS_EHIP, "no HIP device");
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t H = f.hidden, I = f.mlp_inter;
+    char* p = reinterpret_cast<char*>(dst);
+    auto copy = [&](const void* s, size_t bytes, const void** slot) -> hipError_t {
+        *slot = p;
+        hipError_t e = hipMemcpyAsync(p, s, bytes, hipMemcpyDeviceToDevice, st);
+        p += align_up(bytes, 256);
+        return e;
+    };
+    rs_layer_weights o{};
+    RS_HIP(copy(src->ln1_g, H * 2, &o.ln1_g));
+    RS_HIP(copy(src->ln2_g, H * 2, &o.ln2_g));
+    RS_HIP(copy(src->w_qkv, (size_t)c->qkv_dim * H * 2, &o.w_qkv));
+    if (f.qkv_bias) {
+        RS_HIP(copy(src->b_qkv, (size_t)c->qkv_dim * 2, &o.b_qkv));
+    } else {
+        p += align_up((size_t)c->qkv_dim * 2, 256);
+    }
+    RS_HIP(copy(src->w_o, H * c->q_dim * 2, &o.w_o));
+    o.w_gate_up = p;
+    hipLaunchKernelGGL(pack_gate_up_kernel, dim3(2 * f.mlp_inter), dim3(256), 0, st, (const bf16*)src->w_gate_up,
+                       reinterpret_cast<bf16*>(p), f.mlp_inter, f.hidden);
+    RS_HIP(hipGetLastError());
+    p += align_up(2 * I * H * 2, 256);
+    RS_HIP(copy(src->w_down, H * I * 2, &o.w_down));
+    *packed = o;
+    return RS_OK;
+}
+
+size_t rs_kv_bytes(const rs_ctx* c, int n_layers, int capacity_tokens) {
+    if (!c || n_layers <= 0 || capacity_tokens <= 0) return 0;
+    const size_t cap = align_up((size_t)capacity_tokens, 64);
+    const size_t plane = align_up(cap * c->kv_dim * 2, 256);
+    return 2 * plane * n_layers;
+}
+
+rs_status rs_kv_alloc(rs_ctx* c, int n_layers, int capacity_tokens, void* dev_mem, size_t bytes, rs_kv** out) {
+    if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
+    *out = nullptr;
+    if (n_layers <= 0 || capacity_tokens <= 0) return fail(RS_EINVAL, "n_layers and capacity_tokens must be positive");
+    if (!dev_mem || !aligned(dev_mem, 256)) return fail(RS_EINVAL, "dev_mem must be a 256-byte aligned device pointer");
+    const size_t need = rs_kv_bytes(c, n_layers, capacity_tokens);
+    if (bytes < need) return fail(RS_EWORKSPACE, "KV slab has %zu bytes, need %zu", bytes, need);
+    rs_kv* kv = new rs_kv();
+    kv->ctx = c;
+    kv->n_layers = n_layers;
+    kv->cap = (int)align_up((size_t)capacity_tokens, 64);
+    kv->base = reinterpret_cast<char*>(dev_mem);
+    kv->k_bytes = align_up((size_t)kv->cap * c->kv_dim * 2, 256);
+    kv->layer_bytes = 2 * kv->k_bytes;
+    kv->len.assign(n_layers, 0);
+    *out = kv;
+    return RS_OK;
+}
+
+void rs_kv_free(rs_kv* kv) { delete kv; }
+
+int rs_kv_len(const rs_kv* kv, int layer) {
+    if (!kv || layer < 0 || layer >= kv->n_layers) return -1;
+    return kv->len[layer];
+}
+
+int rs_kv_capacity(const rs_kv* kv) { return kv ? kv->cap : -1; }
+
+rs_status rs_kv_reset(rs_kv* kv) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    std::fill(kv->len.begin(), kv->len.end(), 0);
+    return RS_OK;
+}
+
+rs_status rs_kv_truncate(rs_kv* kv, int layer, int n_tokens) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    if (n_tokens < 0 || n_tokens > kv->len[layer]) return fail(RS_EINVAL, "n_tokens = %d outside [0, %d]", n_tokens, kv->len[layer]);
+    kv->len[layer] = n_tokens;
+    return RS_OK;
+}
+
+rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out, void* v_out, void* stream) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    const int n = kv->len[layer];
+    if (n == 0) return RS_OK;
+    if (!k_out || !v_out) return fail(RS_EINVAL, "k_out / v_out is null");
+    if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
+    const rs_layer_cfg& f = kv->ctx->cfg;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t total = (size_t)n * kv->ctx->kv_dim;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    if (f.head_dim == 128)
+        hipLaunchKernelGGL(kv_export_kernel<128>, dim3(blocks), dim3(256), 0, st, (const bf16*)kv->k_of(layer), (const bf16*)kv->vt_of(layer),
+                           (bf16*)k_out, (bf16*)v_out, n, f.n_kv_heads, kv->cap);
+    else
+        hipLaunchKernelGGL(kv_export_kernel<64>, dim3(blocks), dim3(256), 0, st, (const bf16*)kv->k_of(layer), (const bf16*)kv->vt_of(layer),
+                           (bf16*)k_out, (bf16*)v_out, n, f.n_kv_heads, kv->cap);
+    RS_HIP(hipGetLastError());
+    return RS_OK;
+}
+
+rs_status rs_kv_import(rs_kv* kv, int layer, const void* k, const void* v, int n_tokens, void* stream) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
+    if (n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
+    if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
+    if (n_tokens == 0) {
+        kv->len[layer] = 0;
+        return RS_OK;
+    }
+    if (!k || !v) return fail(RS_EINVAL, "k / v is null");
+    if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
+    const rs_layer_cfg& f = kv->ctx->cfg;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t total = align_up((size_t)n_tokens, 64) * kv->ctx->kv_dim;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    if (f.head_dim == 128)
+        hipLaunchKernelGGL(kv_import_kernel<128>, dim3(blocks), dim3(256), 0, st, kv->k_of(layer), kv->vt_of(layer), (const bf16*)k,
+                           (const bf16*)v, n_tokens, f.n_kv_heads, kv->cap);
+    else
+        hipLaunchKernelGGL(kv_import_kernel<64>, dim3(blocks), dim3(256), 0, st, kv->k_of(layer), kv->vt_of(layer), (const bf16*)k,
+                           (const bf16*)v, n_tokens, f.n_kv_heads, kv->cap);
+    RS_HIP(hipGetLastError());
+    kv->len[layer] = n_tokens;
+    return RS_OK;
+}
+
+rs_status rs_profile_enable(rs_ctx* c, int step, int max_launches) {
+    if (!c) return fail(RS_EINVAL, "ctx is null");
+    if (step < -1 || step >= RS_STEP_COUNT) return fail(RS_EINVAL, "step %d out of range", step);
+    if (step >= 0 && max_launches <= 0) return fail(RS_EINVAL, "max_launches must be positive");
+    if (step >= 0 && !c->has_device) return fail(RS_EHIP, "no HIP device");
+    c->prof_step = step;
+    c->prof_count = 0;
+    while (step >= 0 && (int)c->prof_events.size() < 2 * max_launches) {
+        hipEvent_t e;
+        RS_HIP(hipEventCreate(&e));
+        c->prof_events.push_back(e);
+    }
+    return RS_OK;
+}
+
+rs_status rs_profile_read(rs_ctx* c, double* total_ms, int* launches) {
+    if (!c || !total_ms || !launches) return fail(RS_EINVAL, "null argument");
+    double sum = 0.0;
+    for (int i = 0; i < c->prof_count; ++i) {
+        RS_HIP(hipEventSynchronize(c->prof_events[2 * i + 1]));
+        float ms = 0.0f;
+        RS_HIP(hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = c->prof_count;
+    c->prof_count = 0;
+    return RS_OK;
+}
+
+size_t rs_workspace_bytes(const rs_ctx* c, int max_tokens, int max_requests) {
+    if (!c || max_tokens <= 0 || max_requests <= 0) return 0;
+    return ws_layout(c, max_tokens, max_requests).total;
+}
+
+rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv, const void* x, int T, void* y,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (T < 0) return fail(RS_EINVAL, "T = %d is negative", T);
+    rs_kv* kvs[1] = {kv};
+    int lens[1] = {T};
+    return prefill_impl(ctx, packed, layer, kvs, lens, 1, x, y, workspace, workspace_bytes, stream);
+}
+
+rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* const* kvs, const int* chunk_lens, int R,
+                           const void* x, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_impl(ctx, packed, layer, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

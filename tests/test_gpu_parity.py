@@ -1,0 +1,327 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle on the same seeded inputs.
+
+Bar (per layer output Y, and per layer K~ and V cache): relative Frobenius error <= 1e-2.  bf16 storage with fp32
+accumulation rounds each stored intermediate to 2^-9 relative; a handful of such roundings per layer stays well
+inside 1e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from oracle import ChunkedPrefill, LayerParams, layer_forward, layer_forward_rows, prefill_batch, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+def _runner():
+    from paper_2509_24381_amd import runner
+    return runner
+
+
+def _dev(a):
+    return _runner().to_device_bf16(a)
+
+
+def _np(t):
+    return _runner().to_numpy_f32(t)
+
+
+def check(name, got, want, tol=TOL):
+    err = rel_fro(got, want)
+    print(f"[parity] {name}: rel_fro = {err:.3e}", flush=True)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    assert err <= tol, f"{name}: rel_fro {err:.3e} > {tol}"
+    return err
+
+
+def run_single_request(shape, weights_per_layer, x, chunks, *, capacity=None, qkv_bias=False, max_tokens=None):
+    """GPU: one request, all layers, chunk by chunk.  Returns per-layer (Y, K~, V) as float32 numpy."""
+    R = _runner()
+    n = x.shape[0]
+    budget = max(b - a for a, b in chunks) if max_tokens is None else max_tokens
+    stack = R.LayerStack(shape, weights_per_layer, max_tokens=budget, max_requests=4, max_pos=max(n, 64),
+                         qkv_bias=qkv_bias)
+    kv = stack.new_cache(capacity or n)
+    x_dev = _dev(x)
+    _, outs = stack.prefill_prompt(x_dev, chunks, kv, keep_layer_outputs=True)
+    torch.cuda.synchronize()
+    res = []
+    for l in range(stack.n_layers):
+        assert kv.length(l) == n
+        k, v = kv.export(l)
+        res.append((_np(outs[l]), _np(k), _np(v)))
+    return res
+
+
+# ------------------------------------------------------------------ stage isolation on the tiny shape
+def tiny_inputs(n=200, seed=1, **kw):
+    shape = synth.TINY
+    w = synth.layer_weights(shape, seed, **kw)
+    x = synth.prompt_rows([("image", n // 2), ("text", n - n // 2)], shape.hidden, seed + 1)
+    return shape, w, x
+
+
+def test_residual_only_path_is_identity():
+    """W_o = 0 and W_d = 0: both residual GEMM epilogues must return x exactly (bit-exact in bf16)."""
+    shape, w, x = tiny_inputs(n=130)
+    w.wo = np.zeros_like(w.wo)
+    w.wd = np.zeros_like(w.wd)
+    (y, k, v), = run_single_request(shape, [w], x, [(0, 130)])
+    np.testing.assert_array_equal(y, x)
+
+
+def test_cache_content_isolates_norm_qkv_rope_append():
+    """K~/V depend only on RMSNorm, the QKV GEMM, RoPE and the append kernels."""
+    shape, w, x = tiny_inputs(n=333, seed=3, qkv_bias=True, gains="uniform")
+    p = LayerParams.from_arrays(shape, w)
+    _, k_ref, v_ref = layer_forward(x, p)
+    (y, k, v), = run_single_request(shape, [w], x, [(0, 100), (100, 101), (101, 333)], qkv_bias=True)
+    check("tiny K cache", k, k_ref)
+    check("tiny V cache", v, v_ref)
+
+
+def test_attention_and_output_projection_isolated():
+    """W_d = 0: y = x + attention @ W_o^T."""
+    shape, w, x = tiny_inputs(n=300, seed=5)
+    w.wd = np.zeros_like(w.wd)
+    p = LayerParams.from_arrays(shape, w)
+    y_ref, _, _ = layer_forward(x, p)
+    (y, _, _), = run_single_request(shape, [w], x, [(0, 77), (77, 300)])
+    check("tiny y (no MLP)", y, y_ref)
+    # on text rows |x| is small, so the bf16 rounding of y does not swamp the attention term
+    check("tiny attention contribution (text rows)", (y - x)[150:], (y_ref - x)[150:], tol=2e-2)
+
+
+# ------------------------------------------------------------------ workload 1: tiny, element by element
+def test_workload1_tiny_full():
+    wl = synth.workload(1)
+    w = wl.weights(0)
+    x = wl.prompt()
+    p = LayerParams.from_arrays(wl.shape, w)
+    y_ref, k_ref, v_ref = layer_forward(x, p)
+    (y, k, v), = run_single_request(wl.shape, [w], x, wl.chunks())
+    check("w1 Y", y, y_ref)
+    check("w1 K", k, k_ref)
+    check("w1 V", v, v_ref)
+    # text rows are ~50x smaller than image rows: check them on their own so they cannot hide in the norm
+    check("w1 Y text rows", y[256:], y_ref[256:])
+    check("w1 Y image rows", y[:256], y_ref[:256])
+
+
+@pytest.mark.parametrize("chunks", [[(0, 512)], [(0, 1), (1, 2), (2, 65), (65, 129), (129, 512)], [(0, 255), (255, 257), (257, 512)]])
+def test_chunking_invariance_on_gpu(chunks):
+    """Any chunking gives the same layer (section 2.2.1): compare each against the unchunked oracle."""
+    wl = synth.workload(1)
+    w = wl.weights(0, qkv_bias=True, gains="uniform")
+    x = wl.prompt()
+    p = LayerParams.from_arrays(wl.shape, w)
+    y_ref, k_ref, v_ref = layer_forward(x, p)
+    (y, k, v), = run_single_request(wl.shape, [w], x, chunks, qkv_bias=True, max_tokens=512)
+    check(f"chunks={len(chunks)} Y", y, y_ref)
+    check(f"chunks={len(chunks)} K", k, k_ref)
+    check(f"chunks={len(chunks)} V", v, v_ref)
+
+
+def test_gpu_is_deterministic():
+    wl = synth.workload(1)
+    w = wl.weights(0)
+    x = wl.prompt()
+    a = run_single_request(wl.shape, [w], x, wl.chunks())
+    b = run_single_request(wl.shape, [w], x, wl.chunks())
+    for (ya, ka, va), (yb, kb, vb) in zip(a, b):
+        np.testing.assert_array_equal(ya, yb)
+        np.testing.assert_array_equal(ka, kb)
+        np.testing.assert_array_equal(va, vb)
+
+
+def test_tiny_two_layers_and_head_dim_128():
+    """A small shape with head_dim 128 and group 4, two stacked layers, ragged chunk sizes."""
+    shape = synth.LayerShape("small128", 512, 8, 2, 128, 768)
+    ws = [synth.layer_weights(shape, 40 + l, gains="uniform") for l in range(2)]
+    x = synth.prompt_rows([("text", 30), ("image", 300), ("text", 91)], shape.hidden, 44)
+    chunks = [(0, 190), (190, 191), (191, 421)]
+    res = run_single_request(shape, ws, x, chunks, max_tokens=230)
+    cur = x
+    for l in range(2):
+        y_ref, k_ref, v_ref = layer_forward(cur, LayerParams.from_arrays(shape, ws[l]))
+        check(f"small128 layer {l} Y", res[l][0], y_ref)
+        check(f"small128 layer {l} K", res[l][1], k_ref)
+        check(f"small128 layer {l} V", res[l][2], v_ref)
+        cur = y_ref
+
+
+# ------------------------------------------------------------------ micro-batches (Algorithm 2's S)
+def run_batch(shape, w, reqs, *, capacity, order=None):
+    R = _runner()
+    total = sum(r.rows.shape[0] for r in reqs)
+    stack = R.LayerStack(shape, [w], max_tokens=max(total, 1), max_requests=max(len(reqs), 1),
+                         max_pos=capacity)
+    kvs = []
+    for r in reqs:
+        kv = stack.new_cache(capacity)
+        if r.prior_len:
+            kv.import_(0, _dev(r.prior_k), _dev(r.prior_v))
+        kvs.append(kv)
+    x = np.concatenate([r.rows for r in reqs], axis=0)
+    y = stack.prefill_batch(0, kvs, [r.rows.shape[0] for r in reqs], _dev(x))
+    torch.cuda.synchronize()
+    caches = []
+    for kv, r in zip(kvs, reqs):
+        assert kv.length(0) == r.prior_len + r.rows.shape[0]
+        k, v = kv.export(0)
+        caches.append((_np(k), _np(v)))
+    return _np(y), caches
+
+
+def oracle_batch(shape, w, reqs):
+    p = LayerParams.from_arrays(shape, w)
+    states = [ChunkedPrefill(p, r.prior_k, r.prior_v) for r in reqs]
+    y = prefill_batch(states, [r.rows for r in reqs])
+    return y, [(s.k, s.v) for s in states]
+
+
+def test_small_ragged_batch_with_empty_and_single_row_requests():
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 77, gains="uniform")
+    rng = np.random.default_rng(78)
+    spec = [(0, 5), (130, 1), (64, 0), (63, 200), (1, 64), (300, 37)]   # (prior_len, T)
+    reqs = []
+    for prior, t in spec:
+        pk = synth.bf16_round(rng.standard_normal((prior, 2, 64), dtype=np.float32))
+        pv = synth.bf16_round(rng.standard_normal((prior, 2, 64), dtype=np.float32))
+        rows = synth.bf16_round(rng.standard_normal((t, 256), dtype=np.float32) * np.float32(0.5))
+        reqs.append(synth.BatchRequest(prior, pk, pv, rows))
+    y, caches = run_batch(shape, w, reqs, capacity=512)
+    y_ref, caches_ref = oracle_batch(shape, w, reqs)
+    check("ragged batch Y", y, y_ref)
+    off = 0
+    for i, (r, (k, v), (k_ref, v_ref)) in enumerate(zip(reqs, caches, caches_ref)):
+        t = r.rows.shape[0]
+        if t:
+            check(f"ragged batch Y req {i}", y[off: off + t], y_ref[off: off + t])
+        if k_ref.shape[0]:
+            check(f"ragged batch K req {i}", k, k_ref)
+            check(f"ragged batch V req {i}", v, v_ref)
+            # the imported prefix must come back bit-exact
+            np.testing.assert_array_equal(k[: r.prior_len], r.prior_k)
+            np.testing.assert_array_equal(v[: r.prior_len], r.prior_v)
+        off += t
+
+
+# ------------------------------------------------------------------ production shapes
+def test_workload2_7b_2048_budget512():
+    wl = synth.workload(2)
+    w = wl.weights(0)
+    x = wl.prompt()
+    p = LayerParams.from_arrays(wl.shape, w)
+    y_ref, k_ref, v_ref = layer_forward(x, p)
+    (y, k, v), = run_single_request(wl.shape, [w], x, wl.chunks())
+    check("w2 Y", y, y_ref)
+    check("w2 K", k, k_ref)
+    check("w2 V", v, v_ref)
+    # diagnostic beyond the stated bar: text rows alone (about 2% of the output's norm).  Their residual stream is
+    # dominated by the attention term, whose bf16 q/k roundings the MLP then amplifies; a numpy emulation of the
+    # kernel's rounding points gives 1.1e-2 here, so the guard sits at 2e-2.
+    check("w2 Y text rows", y[1280:], y_ref[1280:], tol=2e-2)
+
+
+def test_workload4_7b_batch16():
+    wl = synth.workload(4)
+    w = wl.weights(0)
+    reqs = wl.batch()
+    assert sum(r.rows.shape[0] for r in reqs) == 2048
+    y, caches = run_batch(wl.shape, w, reqs, capacity=12288 + 2048)
+    y_ref, caches_ref = oracle_batch(wl.shape, w, reqs)
+    check("w4 Y pooled", y, y_ref)
+    off = 0
+    for i, (r, (k, v), (k_ref, v_ref)) in enumerate(zip(reqs, caches, caches_ref)):
+        t = r.rows.shape[0]
+        check(f"w4 Y req {i} (P={r.prior_len}, T={t})", y[off: off + t], y_ref[off: off + t])
+        check(f"w4 K req {i}", k[r.prior_len:], k_ref[r.prior_len:])
+        check(f"w4 V req {i}", v[r.prior_len:], v_ref[r.prior_len:])
+        np.testing.assert_array_equal(k[: r.prior_len], r.prior_k)
+        off += t
+
+
+def test_workload3_7b_four_layers_8192_budget2048():
+    """The benchmark workload in the benchmark's launch configuration (4 chunks of 2048 through 4 stacked layers).
+
+    Layers hand each other bf16 [T, H] tensors (the ABI's output type), so the oracle chain is fed, layer by layer,
+    its own previous output rounded to bf16 by the input generator.  Two comparisons per layer:
+      * per-layer bar: the GPU layer run on exactly that input (same input on both sides) must meet 1e-2 on Y, K~, V;
+      * end-to-end: the GPU stack running on its own activations drifts from the oracle chain; independent per-layer
+        errors add in quadrature, so layer l is held to 1e-2 * sqrt(l + 1).
+    """
+    R = _runner()
+    wl = synth.workload(3)
+    ws = [wl.weights(l) for l in range(wl.n_layers)]
+    x = wl.prompt()
+    n = x.shape[0]
+    stack = R.LayerStack(wl.shape, ws, max_tokens=wl.budget, max_requests=1, max_pos=n)
+    kv = stack.new_cache(n)
+    _, outs = stack.prefill_prompt(_dev(x), wl.chunks(), kv, keep_layer_outputs=True)
+    torch.cuda.synchronize()
+    e2e = []
+    for l in range(wl.n_layers):
+        k, v = kv.export(l)
+        e2e.append((_np(outs[l]), _np(k), _np(v)))
+    del outs
+    kv_tf = stack.new_cache(n)
+    cur = x
+    for l in range(wl.n_layers):
+        p = LayerParams.from_arrays(wl.shape, ws[l])
+        y_ref, k_ref, v_ref = layer_forward(cur, p)
+        del p
+        if l == 0:
+            y_tf, k_tf, v_tf = e2e[0]
+        else:
+            cur_dev = _dev(cur)
+            y_dev = torch.empty_like(cur_dev)
+            for a, b in wl.chunks():
+                stack.ctx.prefill_chunk(stack.layers[l], l, kv_tf, cur_dev[a:b], y_dev[a:b], stack.ws)
+            torch.cuda.synchronize()
+            kd, vd = kv_tf.export(l)
+            y_tf, k_tf, v_tf = _np(y_dev), _np(kd), _np(vd)
+        check(f"w3 layer {l} Y (same input)", y_tf, y_ref)
+        check(f"w3 layer {l} K (same input)", k_tf, k_ref)
+        check(f"w3 layer {l} V (same input)", v_tf, v_ref)
+        drift_tol = TOL * float(np.sqrt(l + 1))
+        check(f"w3 layer {l} Y (end to end)", e2e[l][0], y_ref, tol=drift_tol)
+        check(f"w3 layer {l} K (end to end)", e2e[l][1], k_ref, tol=drift_tol)
+        check(f"w3 layer {l} V (end to end)", e2e[l][2], v_ref, tol=drift_tol)
+        cur = synth.bf16_round(y_ref.astype(np.float32))
+
+
+def test_workload5_72b_32768_sampled_rows():
+    """72B-shaped layer, 32768-token prompt, 8 chunks of 4096 (the last chunks attend to > 28k cached tokens).
+
+    The whole K~/V cache is compared element by element.  The full fp64 layer is too slow to run whole, so Y is compared
+    on rows the oracle evaluates one by one: a seeded uniform sample (an unbiased estimate of the pooled error, held
+    to the 1e-2 bar) plus hand-picked edge rows (first rows, both sides of every kind of chunk boundary, the
+    image/text boundary, the last row), each of which is held on its own to 3e-2: a single row has no averaging over
+    rows, and text rows (small |x|, output dominated by the attention term) sit near 1e-2 by themselves.
+    """
+    wl = synth.workload(5)
+    w = wl.weights(0)
+    x = wl.prompt()
+    (y, k, v), = run_single_request(wl.shape, [w], x, wl.chunks())
+    rng = np.random.default_rng(5)
+    uniform = sorted(rng.choice(wl.n_tokens, size=40, replace=False).tolist())
+    edges = [0, 1, 255, 256, 4095, 4096, 4097, 16383, 16384, 28671, 28672, 30719, 30720, 30721, 32767]
+    rows = sorted(set(uniform) | set(edges))
+    p = LayerParams.from_arrays(wl.shape, w)
+    y_rows, k_ref, v_ref = layer_forward_rows(x, p, rows)
+    check("w5 K", k, k_ref)
+    check("w5 V", v, v_ref)
+    idx = {r: i for i, r in enumerate(rows)}
+    sel = [idx[r] for r in uniform]
+    check("w5 Y uniform row sample", y[uniform], y_rows[sel])
+    for r in rows:
+        e = rel_fro(y[r], y_rows[idx[r]])
+        kind = "text" if r >= 30720 else "image"
+        print(f"[parity] w5 row {r} ({kind}): rel_fro = {e:.3e}", flush=True)
+        assert e <= 3e-2, f"w5 row {r}: rel_fro {e:.3e}"
