@@ -144,16 +144,14 @@ rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int laye
 
 /* Measurement hook.  The steps of one rs_prefill_* call, in launch order: */
 typedef enum rs_step {
-    RS_STEP_RMSNORM_1 = 0,
-    RS_STEP_QKV_GEMM = 1,
-    RS_STEP_ROPE_APPEND_K = 2,
-    RS_STEP_APPEND_V = 3,
-    RS_STEP_ATTENTION = 4,
-    RS_STEP_O_GEMM = 5,      /* includes its split-K reduction when one is used */
-    RS_STEP_RMSNORM_2 = 6,
-    RS_STEP_GATE_UP_GEMM = 7,
-    RS_STEP_DOWN_GEMM = 8,   /* includes its split-K reduction when one is used */
-    RS_STEP_COUNT = 9
+    RS_STEP_ROW_RMS = 0,       /* 1/rms of the input rows (first RMSNorm; gains are folded into the packed weights) */
+    RS_STEP_QKV_GEMM = 1,      /* QKV projection with the norm factor, bias and RoPE in its epilogue */
+    RS_STEP_APPEND_KV = 2,     /* K copy + transposing V append into the cache */
+    RS_STEP_ATTENTION = 3,
+    RS_STEP_O_GEMM = 4,        /* output projection + residual + second norm's row factors (and split-K reduction, if any) */
+    RS_STEP_GATE_UP_GEMM = 5,  /* gate/up projection with the norm factor and SwiGLU in its epilogue */
+    RS_STEP_DOWN_GEMM = 6,     /* down projection + residual (and split-K reduction, if any) */
+    RS_STEP_COUNT = 7
 } rs_step;
 /* rs_profile_enable(ctx, step, n): from now on the first n launches of `step` are bracketed by two HIP events recorded
  * on the call's own stream (step = -1 switches the hook off).  rs_profile_read waits for the recorded events, returns

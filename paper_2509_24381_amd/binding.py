@@ -25,8 +25,7 @@ EXPORTED_SYMBOLS = (
     "rs_profile_enable", "rs_profile_read",
 )
 
-STEPS = ("rmsnorm_1", "qkv_gemm", "rope_append_k", "append_v", "attention", "o_gemm", "rmsnorm_2", "gate_up_gemm",
-         "down_gemm")
+STEPS = ("row_rms", "qkv_gemm", "append_kv", "attention", "o_gemm", "gate_up_gemm", "down_gemm")
 
 
 class RsError(RuntimeError):

@@ -4,8 +4,10 @@
 // feeds 8 consecutive k values of one row.  A 256x256 output tile is owned by one 256-thread workgroup
 // (4 wavefronts in a 2x2 grid, 128x128 per wavefront = 4x4 MFMA tiles of 32x32, 256 fp32 accumulators
 // per lane).  The weight rows ride on the MFMA "A" side and the token rows on the "B" side, so a lane ends
-// up holding one token and runs of 4 consecutive output features: the epilogue (bias, residual, SwiGLU)
-// is lane-local and stores 8-byte bf16 groups.
+// up holding one token and runs of 4 consecutive output features: the epilogue (RMSNorm row factor, bias,
+// RoPE, residual, SwiGLU) is lane-local and stores 8-byte bf16 groups.  RMSNorm is folded into the GEMMs that
+// follow it: its gain is multiplied into the weight columns when the weights are packed and its per-row
+// factor 1/rms multiplies the fp32 accumulators, so the normalised activations are never rounded to bf16.
 //
 // K is walked in slabs of 64.  A slab of either operand is 256 rows x 128 bytes; it is kept in LDS as
 // 16-byte chunks with the chunk index XOR-ed by ((row >> 1) & 7), which makes both the linear 16-byte
@@ -20,9 +22,11 @@
 #include "common.h"
 
 enum GemmEpilogue {
-    EPI_BIAS = 0,      // out = bf16(acc + bias[n])          (bias may be null)
-    EPI_RESIDUAL = 1,  // out = bf16(acc + resid[m, n])
-    EPI_SWIGLU = 2,    // W rows interleaved in 32-row blocks (gate, up, gate, up, ...): out[m, n/2] = bf16(silu(gate) * up)
+    EPI_QKV_ROPE = 0,  // out = bf16(rope(acc * row_scale[m] + bias[n])): RMSNorm's per-row factor applied after the product
+                       // (its gain is folded into W), rotate-half RoPE at row_pos[m] on the q and k heads
+    EPI_RESIDUAL = 1,  // out = bf16(acc + resid[m, n]); optionally per-row sums of squares of the stored values
+    EPI_SWIGLU = 2,    // W rows interleaved in 32-row blocks (gate, up, gate, up, ...):
+                       // out[m, n/2] = bf16(silu(gate * row_scale[m]) * (up * row_scale[m]))
     EPI_PARTIAL = 3    // split-K: fp32 partial sums to partial[split][m][n]
 };
 
@@ -33,6 +37,12 @@ struct GemmArgs {
     const bf16* bias;   // [N] or null
     const bf16* resid;  // [M, ldr]
     float* partial;     // [splits, M, N]
+    const float* row_scale;  // [M] 1/rms of the row (EPI_QKV_ROPE, EPI_SWIGLU)
+    const int* row_pos;      // [M] absolute position of the row (EPI_QKV_ROPE)
+    const float2* rope_cs;   // [max_pos][head_dim/2] (cos, sin)
+    float* rowss;            // EPI_RESIDUAL: [M][N/128] sum of squares of each stored 128-column run, or null
+    int rope_cols;           // columns [0, rope_cols) are q and k heads
+    int head_dim;
     int ldx, ldo, ldr;
     int M, N, K;
     int tiles_m, tiles_n;
@@ -157,6 +167,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
         const int m = m0 + wm * 128 + j * 32 + l32;
         if (m >= a.M) continue;
         if constexpr (EPI == EPI_SWIGLU) {
+            const float sc = a.row_scale[m];
 #pragma unroll
             for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
@@ -165,10 +176,65 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
                     bf16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        o[e] = f32_to_bf16(silu_f32(acc[2 * i2][j][4 * q + e]) * acc[2 * i2 + 1][j][4 * q + e]);
+                        o[e] = f32_to_bf16(silu_f32(acc[2 * i2][j][4 * q + e] * sc) * (acc[2 * i2 + 1][j][4 * q + e] * sc));
                     *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + col) = o;
                 }
+        } else if constexpr (EPI == EPI_QKV_ROPE) {
+            const int nw = n0 + wn * 128;  // this wavefront's 128 features: whole heads of one kind (q, k or v)
+            const float sc = a.row_scale[m];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float b[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (a.bias != nullptr) {
+                        bf16x4 b4 = *reinterpret_cast<const bf16x4*>(a.bias + nw + i * 32 + 8 * q + 4 * half);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) b[e] = bf16_to_f32(b4[e]);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = acc[i][j][4 * q + e] * sc + b[e];
+                }
+            if (nw < a.rope_cols) {
+                const int hd2 = a.head_dim >> 1;
+                const float2* csr = a.rope_cs + (size_t)a.row_pos[m] * hd2;
+                if (a.head_dim == 128) {  // one head per wavefront: column c pairs with c + 64 = two MFMA tiles to the right
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float2 c = csr[i * 32 + 8 * q + 4 * half + e];
+                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 2][j][4 * q + e];
+                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
+                                acc[i + 2][j][4 * q + e] = hi * c.x + lo * c.y;
+                            }
+                } else {  // head_dim 64: two heads per wavefront, column c pairs with c + 32 = the next MFMA tile
+#pragma unroll
+                    for (int i = 0; i < 4; i += 2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float2 c = csr[8 * q + 4 * half + e];
+                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 1][j][4 * q + e];
+                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
+                                acc[i + 1][j][4 * q + e] = hi * c.x + lo * c.y;
+                            }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc[i][j][4 * q + e]);
+                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + nw + i * 32 + 8 * q + 4 * half) = o;
+                }
         } else {
+            float ss = 0.0f;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -181,35 +247,38 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
                         f32x4 o = {v[0], v[1], v[2], v[3]};
                         *reinterpret_cast<f32x4*>(a.partial + ((size_t)split * a.M + m) * a.N + n) = o;
                     } else {
-                        if constexpr (EPI == EPI_BIAS) {
-                            if (a.bias != nullptr) {
-                                bf16x4 b = *reinterpret_cast<const bf16x4*>(a.bias + n);
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(b[e]);
-                            }
-                        } else {
-                            bf16x4 r4 = *reinterpret_cast<const bf16x4*>(a.resid + (size_t)m * a.ldr + n);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(r4[e]);
-                        }
+                        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(a.resid + (size_t)m * a.ldr + n);
                         bf16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e]);
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = f32_to_bf16(v[e] + bf16_to_f32(r4[e]));
+                            const float st = bf16_to_f32(o[e]);
+                            ss += st * st;
+                        }
                         *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + n) = o;
                     }
                 }
+            if constexpr (EPI == EPI_RESIDUAL) {
+                if (a.rowss != nullptr) {  // the two half-waves hold the two halves of this token's 128-column run
+                    ss += __shfl_xor(ss, 32, WAVE);
+                    if (half == 0) a.rowss[(size_t)m * (a.N / 128) + (n0 + wn * 128) / 128] = ss;
+                }
+            }
         }
     }
 }
 
 // Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).
+// One wavefront per row; when inv_rms is given it also leaves rsqrt(mean(out[m,:]^2) + eps) of the stored row there.
 __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float* __restrict__ partial, int splits,
                                                                      const bf16* __restrict__ resid, int ldr,
-                                                                     bf16* __restrict__ out, int ldo, int M, int N) {
-    const size_t quads = (size_t)M * (N / 4);
-    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
-        const int m = (int)(q / (N / 4));
-        const int n = (int)(q % (N / 4)) * 4;
+                                                                     bf16* __restrict__ out, int ldo, int M, int N,
+                                                                     float* __restrict__ inv_rms, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    float ss = 0.0f;
+    for (int n = lane * 4; n < N; n += WAVE * 4) {
         bf16x4 r4 = *reinterpret_cast<const bf16x4*>(resid + (size_t)m * ldr + n);
         float v[4] = {bf16_to_f32(r4[0]), bf16_to_f32(r4[1]), bf16_to_f32(r4[2]), bf16_to_f32(r4[3])};
         for (int s = 0; s < splits; ++s) {
@@ -217,6 +286,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float
             v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
         }
         bf16x4 o = {f32_to_bf16(v[0]), f32_to_bf16(v[1]), f32_to_bf16(v[2]), f32_to_bf16(v[3])};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float st = bf16_to_f32(o[e]);
+            ss += st * st;
+        }
         *reinterpret_cast<bf16x4*>(out + (size_t)m * ldo + n) = o;
     }
+    if (inv_rms != nullptr) {
+        ss = wave_sum(ss);
+        if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)N + eps);
+    }
+}
+
+// inv_rms[m] = rsqrt(sum_b rowss[m][b] / H + eps): closes the per-row sum of squares left by the EPI_RESIDUAL epilogue.
+__global__ __launch_bounds__(256) void rowss_finalize_kernel(const float* __restrict__ rowss, int blocks_per_row, int M, int H,
+                                                             float eps, float* __restrict__ inv_rms) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    float ss = 0.0f;
+    for (int b = 0; b < blocks_per_row; ++b) ss += rowss[(size_t)m * blocks_per_row + b];
+    inv_rms[m] = rsqrtf(ss / (float)H + eps);
 }

@@ -78,7 +78,7 @@ struct rs_kv {
 namespace {
 
 struct DescSizes {
-    size_t reqs, items, vblocks, total;
+    size_t reqs, items, vblocks, rowpos, total;
 };
 
 DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
@@ -87,8 +87,9 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     const size_t n_vb = (size_t)max_tokens / 64 + 2 * (size_t)max_requests + 1;
     d.reqs = align_up(sizeof(ReqDesc) * std::max(max_requests, 1), 256);
     d.items = align_up(sizeof(AttnItem) * n_items, 256);
-    d.vblocks = align_up(sizeof(VBlockItem) * n_vb, 256);
-    d.total = d.reqs + d.items + d.vblocks;
+    d.vblocks = align_up(sizeof(KVBlockItem) * n_vb, 256);
+    d.rowpos = align_up(sizeof(int) * (size_t)std::max(max_tokens, 1), 256);
+    d.total = d.reqs + d.items + d.vblocks + d.rowpos;
     return d;
 }
 
@@ -101,7 +102,7 @@ int choose_splitk(const rs_ctx* c, int tiles, int k_slabs) {
 }
 
 struct WorkspaceLayout {
-    size_t h, qkv, attn, r, act, partial, desc, total;
+    size_t qkv, attn, r, act, partial, inv_rms1, inv_rms2, rowss, desc, total;
 };
 
 WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
@@ -114,12 +115,14 @@ WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
         return o;
     };
     const size_t t = (size_t)std::max(T, 1);
-    w.h = take(t * f.hidden * 2);
     w.qkv = take(t * c->qkv_dim * 2);
     w.attn = take(t * c->q_dim * 2);
     w.r = take(t * f.hidden * 2);
     w.act = take(t * f.mlp_inter * 2);
     w.partial = take(4 * t * f.hidden * 4);  // up to 4 split-K partial planes of [T, H] fp32
+    w.inv_rms1 = take(t * 4);
+    w.inv_rms2 = take(t * 4);
+    w.rowss = take(t * (f.hidden / 128) * 4);
     w.desc = take(desc_sizes(c, T, R).total);
     w.total = off;
     return w;
@@ -137,20 +140,29 @@ rs_status launch_gemm(GemmArgs a, int splits, hipStream_t st) {
     return RS_OK;
 }
 
-// out = resid + X W^T, through split-K partials when that fills the machine better.
+// out = resid + X W^T, through split-K partials when that fills the machine better.  When inv_rms_out is given it
+// receives rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input); rowss is scratch for it.
 rs_status gemm_residual(const rs_ctx* c, const bf16* X, int ldx, const bf16* W, const bf16* resid, bf16* out,
-                        int M, int N, int K, float* partial, hipStream_t st) {
+                        int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, hipStream_t st) {
     GemmArgs a{};
     a.X = X; a.ldx = ldx; a.W = W; a.out = out; a.ldo = N; a.resid = resid; a.ldr = N; a.partial = partial;
     a.M = M; a.N = N; a.K = K;
+    const float eps = c->cfg.rms_eps;
     const int tiles = ((M + GEMM_BM - 1) / GEMM_BM) * (N / GEMM_BN);
     const int splits = choose_splitk(c, tiles, K / GEMM_BK);
-    if (splits == 1) return launch_gemm<EPI_RESIDUAL>(a, 1, st);
+    if (splits == 1) {
+        a.rowss = inv_rms_out ? rowss : nullptr;
+        rs_status s = launch_gemm<EPI_RESIDUAL>(a, 1, st);
+        if (s != RS_OK || !inv_rms_out) return s;
+        hipLaunchKernelGGL(rowss_finalize_kernel, dim3((M + 255) / 256), dim3(256), 0, st, (const float*)rowss, N / 128, M, N,
+                           eps, inv_rms_out);
+        RS_HIP(hipGetLastError());
+        return RS_OK;
+    }
     rs_status s = launch_gemm<EPI_PARTIAL>(a, splits, st);
     if (s != RS_OK) return s;
-    const size_t quads = (size_t)M * (N / 4);
-    const int blocks = (int)std::min<size_t>((quads + 255) / 256, 256 * 8);
-    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3(blocks), dim3(256), 0, st, partial, splits, resid, N, out, N, M, N);
+    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)partial, splits, resid, N,
+                       out, N, M, N, inv_rms_out, eps);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -172,20 +184,15 @@ struct StepTimer {
 };
 
 template <int D>
-rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs, int n_reqs,
-                                const AttnItem* d_items, int n_items, const VBlockItem* d_vb, int n_vb,
-                                int T, hipStream_t st, const StepTimer& tm) {
+rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs,
+                                const AttnItem* d_items, int n_items, const KVBlockItem* d_vb, int n_vb,
+                                hipStream_t st, const StepTimer& tm) {
     const rs_layer_cfg& f = c->cfg;
-    tm.begin(RS_STEP_ROPE_APPEND_K);
-    hipLaunchKernelGGL(rope_append_k_kernel<D>, dim3(T), dim3(256), 0, st, qkv, c->qkv_dim, d_reqs, n_reqs,
-                       (const float2*)c->rope_dev, f.n_q_heads, f.n_kv_heads);
-    RS_HIP(hipGetLastError());
-    tm.end(RS_STEP_ROPE_APPEND_K);
-    tm.begin(RS_STEP_APPEND_V);
-    hipLaunchKernelGGL(append_v_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
+    tm.begin(RS_STEP_APPEND_KV);
+    hipLaunchKernelGGL(append_kv_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
                        d_reqs, d_vb, f.n_q_heads, f.n_kv_heads);
     RS_HIP(hipGetLastError());
-    tm.end(RS_STEP_APPEND_V);
+    tm.end(RS_STEP_APPEND_KV);
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
     tm.begin(RS_STEP_ATTENTION);
     hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
@@ -241,7 +248,9 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     // ---- host descriptors
     std::vector<ReqDesc> reqs;
     std::vector<AttnItem> items;
-    std::vector<VBlockItem> vbs;
+    std::vector<KVBlockItem> vbs;
+    std::vector<int> rowpos;
+    rowpos.reserve(T);
     const int g = ctx->group;
     int row0 = 0;
     for (int i = 0; i < R; ++i) {
@@ -261,7 +270,8 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
             const int nkb = (P + t_max + 1 + ATT_KEYS - 1) / ATT_KEYS;
             for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb});
         }
-        for (int b = P / 64; b <= (P + Ti - 1) / 64; ++b) vbs.push_back(VBlockItem{ri, b});
+        for (int b = P / 64; b <= (P + Ti - 1) / 64; ++b) vbs.push_back(KVBlockItem{ri, b});
+        for (int t = 0; t < Ti; ++t) rowpos.push_back(P + t);
         row0 += Ti;
     }
     // heaviest work first: the tail of the launch is then made of short items
@@ -269,7 +279,7 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
 
     const DescSizes ds = desc_sizes(ctx, T, R);
     if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
-        sizeof(VBlockItem) * vbs.size() > ds.vblocks || ds.total > ctx->slot_bytes)
+        sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos || ds.total > ctx->slot_bytes)
         return fail(RS_EINVAL, "internal: descriptor sizing");
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -278,7 +288,8 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     char* stage = ctx->pinned[slot];
     memcpy(stage, reqs.data(), sizeof(ReqDesc) * reqs.size());
     memcpy(stage + ds.reqs, items.data(), sizeof(AttnItem) * items.size());
-    memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(VBlockItem) * vbs.size());
+    memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(KVBlockItem) * vbs.size());
+    memcpy(stage + ds.reqs + ds.items + ds.vblocks, rowpos.data(), sizeof(int) * rowpos.size());
     char* wsb = reinterpret_cast<char*>(ws);
     RS_HIP(hipMemcpyAsync(wsb + L.desc, stage, ds.total, hipMemcpyHostToDevice, st));
     RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
@@ -286,62 +297,63 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     ctx->next_slot = (slot + 1) % RING_SLOTS;
     const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
     const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
-    const VBlockItem* d_vb = reinterpret_cast<const VBlockItem*>(wsb + L.desc + ds.reqs + ds.items);
+    const KVBlockItem* d_vb = reinterpret_cast<const KVBlockItem*>(wsb + L.desc + ds.reqs + ds.items);
+    const int* d_rowpos = reinterpret_cast<const int*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks);
 
-    bf16* h = reinterpret_cast<bf16*>(wsb + L.h);
     bf16* qkv = reinterpret_cast<bf16*>(wsb + L.qkv);
     bf16* attn = reinterpret_cast<bf16*>(wsb + L.attn);
     bf16* r = reinterpret_cast<bf16*>(wsb + L.r);
     bf16* act = reinterpret_cast<bf16*>(wsb + L.act);
     float* partial = reinterpret_cast<float*>(wsb + L.partial);
+    float* inv_rms1 = reinterpret_cast<float*>(wsb + L.inv_rms1);
+    float* inv_rms2 = reinterpret_cast<float*>(wsb + L.inv_rms2);
+    float* rowss = reinterpret_cast<float*>(wsb + L.rowss);
     const bf16* xb = reinterpret_cast<const bf16*>(x);
     bf16* yb = reinterpret_cast<bf16*>(y);
     const int H = f.hidden, I = f.mlp_inter;
     rs_status s;
     const StepTimer tm{ctx, st};
 
-    // h = rmsnorm(x; g1)
-    tm.begin(RS_STEP_RMSNORM_1);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, st, xb, (const bf16*)w->ln1_g, h, T, H, f.rms_eps);
+    // 1/rms of every input row (the first RMSNorm; its gain lives in the packed W_qkv)
+    tm.begin(RS_STEP_ROW_RMS);
+    hipLaunchKernelGGL(row_inv_rms_kernel, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv_rms1, T, H, f.rms_eps);
     RS_HIP(hipGetLastError());
-    tm.end(RS_STEP_RMSNORM_1);
-    // qkv = h Wqkv^T (+ b)
+    tm.end(RS_STEP_ROW_RMS);
+    // qkv = rope( (x Wqkv'^T) / rms + b )
     tm.begin(RS_STEP_QKV_GEMM);
     {
         GemmArgs a{};
-        a.X = h; a.ldx = H; a.W = (const bf16*)w->w_qkv; a.out = qkv; a.ldo = ctx->qkv_dim;
+        a.X = xb; a.ldx = H; a.W = (const bf16*)w->w_qkv; a.out = qkv; a.ldo = ctx->qkv_dim;
         a.bias = f.qkv_bias ? (const bf16*)w->b_qkv : nullptr;
+        a.row_scale = inv_rms1; a.row_pos = d_rowpos; a.rope_cs = (const float2*)ctx->rope_dev;
+        a.rope_cols = ctx->q_dim + ctx->kv_dim; a.head_dim = f.head_dim;
         a.M = T; a.N = ctx->qkv_dim; a.K = H;
-        if ((s = launch_gemm<EPI_BIAS>(a, 1, st)) != RS_OK) return s;
+        if ((s = launch_gemm<EPI_QKV_ROPE>(a, 1, st)) != RS_OK) return s;
     }
     tm.end(RS_STEP_QKV_GEMM);
-    // RoPE, cache append, attention
+    // cache append, attention
     if (f.head_dim == 128)
-        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, (int)reqs.size(), d_items, (int)items.size(), d_vb, (int)vbs.size(), T, st, tm);
+        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), st, tm);
     else
-        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, (int)reqs.size(), d_items, (int)items.size(), d_vb, (int)vbs.size(), T, st, tm);
+        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), st, tm);
     if (s != RS_OK) return s;
-    // r = x + attn Wo^T
+    // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
-    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, inv_rms2, rowss, st)) != RS_OK) return s;
     tm.end(RS_STEP_O_GEMM);
-    // h2 = rmsnorm(r; g2)
-    tm.begin(RS_STEP_RMSNORM_2);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16*)r, (const bf16*)w->ln2_g, h, T, H, f.rms_eps);
-    RS_HIP(hipGetLastError());
-    tm.end(RS_STEP_RMSNORM_2);
-    // act = silu(h2 Wg^T) * (h2 Wu^T)
+    // act = silu((r Wg'^T) / rms) * ((r Wu'^T) / rms)
     tm.begin(RS_STEP_GATE_UP_GEMM);
     {
         GemmArgs a{};
-        a.X = h; a.ldx = H; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I;
+        a.X = r; a.ldx = H; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I;
+        a.row_scale = inv_rms2;
         a.M = T; a.N = 2 * I; a.K = H;
         if ((s = launch_gemm<EPI_SWIGLU>(a, 1, st)) != RS_OK) return s;
     }
     tm.end(RS_STEP_GATE_UP_GEMM);
     // y = r + act Wd^T
     tm.begin(RS_STEP_DOWN_GEMM);
-    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, nullptr, nullptr, st)) != RS_OK) return s;
     tm.end(RS_STEP_DOWN_GEMM);
 
     for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
@@ -369,6 +381,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (f.hidden % 256) return fail(RS_EINVAL, "hidden must be a multiple of 256");
     if (qkv_dim % 256) return fail(RS_EINVAL, "(Hq + 2 Hkv) * head_dim must be a multiple of 256");
     if (f.mlp_inter % 128) return fail(RS_EINVAL, "mlp_inter must be a multiple of 128");
+    if (q_dim % 128 || kv_dim % 128) return fail(RS_EINVAL, "Hq * head_dim and Hkv * head_dim must be multiples of 128");
     if (!(f.rms_eps >= 0.0f) || !(f.rope_theta > 0.0f)) return fail(RS_EINVAL, "rms_eps / rope_theta out of range");
     if ((size_t)f.max_tokens_per_call * (size_t)std::max(qkv_dim, f.mlp_inter) * 2 >= (size_t)1 << 31)
         return fail(RS_EINVAL, "max_tokens_per_call too large for 32-bit row offsets");
@@ -413,7 +426,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
     }
     // kernels that use more than 64 KB of LDS must opt in
-    e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_BIAS>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_QKV_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
@@ -457,7 +470,8 @@ rs_status rs_weights_pack(rs_ctx* c, const rs_layer_weights* src, void* dst, siz
         return fail(RS_EINVAL, "a source weight pointer is null");
     if (f.qkv_bias && !src->b_qkv) return fail(RS_EINVAL, "cfg.qkv_bias is set but b_qkv is null");
     if (!aligned(dst, 256)) return fail(RS_EINVAL, "dst must be 256-byte aligned");
-    if (!aligned(src->w_gate_up, 16)) return fail(RS_EINVAL, "w_gate_up must be 16-byte aligned");
+    if (!aligned(src->w_gate_up, 16) || !aligned(src->w_qkv, 16) || !aligned(src->ln1_g, 16) || !aligned(src->ln2_g, 16))
+        return fail(RS_EINVAL, "source weights must be 16-byte aligned");
     if (dst_bytes < rs_weights_packed_bytes(c)) return fail(RS_EWORKSPACE, "dst has %zu bytes, need %zu", dst_bytes, rs_weights_packed_bytes(c));
     if (!c->has_device) return fail(RS_EHIP, "no HIP device");
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -472,16 +486,22 @@ rs_status rs_weights_pack(rs_ctx* c, const rs_layer_weights* src, void* dst, siz
     rs_layer_weights o{};
     RS_HIP(copy(src->ln1_g, H * 2, &o.ln1_g));
     RS_HIP(copy(src->ln2_g, H * 2, &o.ln2_g));
-    RS_HIP(copy(src->w_qkv, (size_t)c->qkv_dim * H * 2, &o.w_qkv));
+    // W_qkv with the first norm's gain folded into its columns
+    o.w_qkv = p;
+    hipLaunchKernelGGL(pack_rows_kernel, dim3(c->qkv_dim), dim3(256), 0, st, (const bf16*)src->w_qkv, (const bf16*)src->ln1_g,
+                       reinterpret_cast<bf16*>(p), f.hidden, 0);
+    RS_HIP(hipGetLastError());
+    p += align_up((size_t)c->qkv_dim * H * 2, 256);
     if (f.qkv_bias) {
         RS_HIP(copy(src->b_qkv, (size_t)c->qkv_dim * 2, &o.b_qkv));
     } else {
         p += align_up((size_t)c->qkv_dim * 2, 256);
     }
     RS_HIP(copy(src->w_o, H * c->q_dim * 2, &o.w_o));
+    // W_gate / W_up interleaved in 32-row blocks, with the second norm's gain folded into their columns
     o.w_gate_up = p;
-    hipLaunchKernelGGL(pack_gate_up_kernel, dim3(2 * f.mlp_inter), dim3(256), 0, st, (const bf16*)src->w_gate_up,
-                       reinterpret_cast<bf16*>(p), f.mlp_inter, f.hidden);
+    hipLaunchKernelGGL(pack_rows_kernel, dim3(2 * f.mlp_inter), dim3(256), 0, st, (const bf16*)src->w_gate_up,
+                       (const bf16*)src->ln2_g, reinterpret_cast<bf16*>(p), f.hidden, f.mlp_inter);
     RS_HIP(hipGetLastError());
     p += align_up(2 * I * H * 2, 256);
     RS_HIP(copy(src->w_down, H * I * 2, &o.w_down));

@@ -81,7 +81,7 @@ def test_sizes_and_kv_bookkeeping(lib):
     # K and V^T planes: capacity rounded up to 64 tokens, Hkv*d*2 bytes per token each, per layer
     assert ctx.kv_bytes(2, 100) == 2 * 2 * 128 * 128 * 2
     assert ctx.kv_bytes(0, 100) == 0
-    assert ctx.workspace_bytes(128, 4) >= 128 * (256 * 2 + 512 + 256 + 1024) * 2
+    assert ctx.workspace_bytes(128, 4) >= 128 * (256 + 512 + 256 + 1024) * 2
     assert ctx.workspace_bytes(128, 4) >= ctx.workspace_bytes(64, 2)
     assert ctx.weights_packed_bytes() >= 2 * (512 * 256 + 256 * 256 + 3 * 256 * 1024)
     kv = make_kv(lib, ctx)
