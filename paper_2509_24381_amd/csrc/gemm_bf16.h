@@ -47,6 +47,9 @@ struct GemmArgs {
     int M, N, K;
     int tiles_m, tiles_n;
     int k_slabs_per_split;  // K/64 slabs handled by one blockIdx.y
+#ifdef RS_GEMM_TIMING
+    unsigned long long* dbg;  // development only: per-workgroup cycle counts of the pipeline's wait points
+#endif
 };
 
 constexpr int GEMM_BM = 256, GEMM_BN = 256, GEMM_BK = 64;
@@ -54,6 +57,117 @@ constexpr int GEMM_STAGE_BYTES = GEMM_BM * GEMM_BK * 2;          // one operand,
 constexpr int GEMM_LDS_BYTES = 4 * GEMM_STAGE_BYTES;             // 2 operands x 2 buffers
 
 RS_DEVICE float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
+
+// Lane-local epilogue shared by the GEMM kernels.  acc[i][j][r] holds token m = m0 + wm*128 + j*32 + l32 and
+// feature n = n0 + wn*128 + i*32 + 8*(r>>2) + 4*half + (r&3).
+template <int EPI>
+RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn, int half, int l32,
+                             int split) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 128 + j * 32 + l32;
+        if (m >= a.M) continue;
+        if constexpr (EPI == EPI_SWIGLU) {
+            const float sc = a.row_scale[m];
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = (n0 + wn * 128) / 2 + i2 * 32 + 8 * q + 4 * half;
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = f32_to_bf16(silu_f32(acc[2 * i2][j][4 * q + e] * sc) * (acc[2 * i2 + 1][j][4 * q + e] * sc));
+                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + col) = o;
+                }
+        } else if constexpr (EPI == EPI_QKV_ROPE) {
+            const int nw = n0 + wn * 128;  // this wavefront's 128 features: whole heads of one kind (q, k or v)
+            const float sc = a.row_scale[m];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float b[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (a.bias != nullptr) {
+                        bf16x4 b4 = *reinterpret_cast<const bf16x4*>(a.bias + nw + i * 32 + 8 * q + 4 * half);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) b[e] = bf16_to_f32(b4[e]);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = acc[i][j][4 * q + e] * sc + b[e];
+                }
+            if (nw < a.rope_cols) {
+                const int hd2 = a.head_dim >> 1;
+                const float2* csr = a.rope_cs + (size_t)a.row_pos[m] * hd2;
+                if (a.head_dim == 128) {  // one head per wavefront: column c pairs with c + 64 = two MFMA tiles to the right
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float2 c = csr[i * 32 + 8 * q + 4 * half + e];
+                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 2][j][4 * q + e];
+                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
+                                acc[i + 2][j][4 * q + e] = hi * c.x + lo * c.y;
+                            }
+                } else {  // head_dim 64: two heads per wavefront, column c pairs with c + 32 = the next MFMA tile
+#pragma unroll
+                    for (int i = 0; i < 4; i += 2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float2 c = csr[8 * q + 4 * half + e];
+                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 1][j][4 * q + e];
+                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
+                                acc[i + 1][j][4 * q + e] = hi * c.x + lo * c.y;
+                            }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc[i][j][4 * q + e]);
+                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + nw + i * 32 + 8 * q + 4 * half) = o;
+                }
+        } else {
+            float ss = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * 128 + i * 32 + 8 * q + 4 * half;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+                    if constexpr (EPI == EPI_PARTIAL) {
+                        f32x4 o = {v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4*>(a.partial + ((size_t)split * a.M + m) * a.N + n) = o;
+                    } else {
+                        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(a.resid + (size_t)m * a.ldr + n);
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = f32_to_bf16(v[e] + bf16_to_f32(r4[e]));
+                            const float st = bf16_to_f32(o[e]);
+                            ss += st * st;
+                        }
+                        *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + n) = o;
+                    }
+                }
+            if constexpr (EPI == EPI_RESIDUAL) {
+                if (a.rowss != nullptr) {  // the two half-waves hold the two halves of this token's 128-column run
+                    ss += __shfl_xor(ss, 32, WAVE);
+                    if (half == 0) a.rowss[(size_t)m * (a.N / 128) + (n0 + wn * 128) / 128] = ss;
+                }
+            }
+        }
+    }
+}
 
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
@@ -160,112 +274,210 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256x256_kernel(GemmArgs a) {
         __syncthreads();
     }
 
-    // ---- epilogue.  acc[i][j][r]: token m = m0 + wm*128 + j*32 + l32,
-    //      feature n = n0 + wn*128 + i*32 + 8*(r>>2) + 4*half + (r&3).
+    gemm_epilogue<EPI>(a, acc, m0, n0, wm, wn, half, l32, split);
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// Same tile, deeper pipeline: operand slabs travel global -> LDS directly (buffer_load ... lds, 16 bytes per lane) through
+// a ring of 4 stages of K=32, so three stages of loads are in flight while one is multiplied and no VGPRs are tied up
+// by data in transit.  Rows past M are outside the buffer resource and read as zeros.
+//
+// A stage of one operand is 256 rows x 64 bytes; 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3) of its row,
+// which keeps the 16 rows a quarter-wave reads at once on 16 different 16-byte bank groups.  A load instruction of one
+// wavefront fills 1 KB of LDS (16 rows) linearly by lane, so each lane fetches the chunk that belongs in its slot.
+//
+// The compiler cannot see through LDS written by DMA (it would wait for every outstanding load before any LDS read),
+// so the fragment reads are inline ds_read_b128 and the waits are explicit:
+//   - loads retire in order; 8 per thread per stage, so "vmcnt(16)" = everything except the two newest stages landed;
+// Each wait is tied by register operands to the fragments it guards, so the MFMAs that consume them cannot move above it.
+// Per stage: 16 MFMAs on the kk=0 fragments with the kk=1 fragment reads and the loads of stage s+3 interleaved one per
+// MFMA, [wait stage s+1, barrier], 16 MFMAs on the kk=1 fragments with the next stage's kk=0 reads behind the first 8.
+constexpr int G2_BK = 32, G2_STAGES = 4;
+constexpr int G2_OP_BYTES = 256 * G2_BK * 2;       // 16 KB
+constexpr int G2_STAGE_BYTES = 2 * G2_OP_BYTES;    // 32 KB
+constexpr int G2_LDS_BYTES = G2_STAGES * G2_STAGE_BYTES;
+
+#define RS_DS_READ_B128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
+
+RS_DEVICE void tie_wait_lgkm8(bf16x8 (&w)[4], bf16x8 (&x)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
+}
+RS_DEVICE void tie_wait_lgkm0(bf16x8 (&w)[4], bf16x8 (&x)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1;
+    const int wm = wave >> 1;
+    const int half = lane >> 5;
+    const int l32 = lane & 31;
+
+    const int nwg = a.tiles_m * a.tiles_n;
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, loc = pid >> 3;
+    const int base = nwg >> 3, rem = nwg & 7;
+    const int logical = (xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base) + loc;
+    const int tm = logical % a.tiles_m;
+    const int tn = logical / a.tiles_m;
+    const int m0 = tm * GEMM_BM;
+    const int n0 = tn * GEMM_BN;
+
+    const int split = blockIdx.y;
+    const int stages_total = a.K / G2_BK;
+    const int st0 = split * a.k_slabs_per_split * 2;                       // a 64-wide slab = 2 stages
+    const int ns = min(a.k_slabs_per_split * 2, stages_total - st0);       // stages this workgroup multiplies (>= 1)
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, a.M * a.ldx * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.W, 0, a.N * a.K * 2, 0x00020000);
+
+    // loader: instruction i of this wavefront fills LDS rows [i*64 + wave*16, +16) of the operand's stage
+    const int ld_r = wave * 16 + (lane >> 2);
+    const int ld_c = (lane & 3) ^ ((lane >> 4) & 3);
+    uint32_t vx[4], vw[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 128 + j * 32 + l32;
-        if (m >= a.M) continue;
-        if constexpr (EPI == EPI_SWIGLU) {
-            const float sc = a.row_scale[m];
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = (n0 + wn * 128) / 2 + i2 * 32 + 8 * q + 4 * half;
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = f32_to_bf16(silu_f32(acc[2 * i2][j][4 * q + e] * sc) * (acc[2 * i2 + 1][j][4 * q + e] * sc));
-                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + col) = o;
-                }
-        } else if constexpr (EPI == EPI_QKV_ROPE) {
-            const int nw = n0 + wn * 128;  // this wavefront's 128 features: whole heads of one kind (q, k or v)
-            const float sc = a.row_scale[m];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float b[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (a.bias != nullptr) {
-                        bf16x4 b4 = *reinterpret_cast<const bf16x4*>(a.bias + nw + i * 32 + 8 * q + 4 * half);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) b[e] = bf16_to_f32(b4[e]);
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = acc[i][j][4 * q + e] * sc + b[e];
-                }
-            if (nw < a.rope_cols) {
-                const int hd2 = a.head_dim >> 1;
-                const float2* csr = a.rope_cs + (size_t)a.row_pos[m] * hd2;
-                if (a.head_dim == 128) {  // one head per wavefront: column c pairs with c + 64 = two MFMA tiles to the right
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float2 c = csr[i * 32 + 8 * q + 4 * half + e];
-                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 2][j][4 * q + e];
-                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
-                                acc[i + 2][j][4 * q + e] = hi * c.x + lo * c.y;
-                            }
-                } else {  // head_dim 64: two heads per wavefront, column c pairs with c + 32 = the next MFMA tile
-#pragma unroll
-                    for (int i = 0; i < 4; i += 2)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float2 c = csr[8 * q + 4 * half + e];
-                                const float lo = acc[i][j][4 * q + e], hi = acc[i + 1][j][4 * q + e];
-                                acc[i][j][4 * q + e] = lo * c.x - hi * c.y;
-                                acc[i + 1][j][4 * q + e] = hi * c.x + lo * c.y;
-                            }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc[i][j][4 * q + e]);
-                    *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + nw + i * 32 + 8 * q + 4 * half) = o;
-                }
-        } else {
-            float ss = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + wn * 128 + i * 32 + 8 * q + 4 * half;
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-                    if constexpr (EPI == EPI_PARTIAL) {
-                        f32x4 o = {v[0], v[1], v[2], v[3]};
-                        *reinterpret_cast<f32x4*>(a.partial + ((size_t)split * a.M + m) * a.N + n) = o;
-                    } else {
-                        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(a.resid + (size_t)m * a.ldr + n);
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            o[e] = f32_to_bf16(v[e] + bf16_to_f32(r4[e]));
-                            const float st = bf16_to_f32(o[e]);
-                            ss += st * st;
-                        }
-                        *reinterpret_cast<bf16x4*>(a.out + (size_t)m * a.ldo + n) = o;
-                    }
-                }
-            if constexpr (EPI == EPI_RESIDUAL) {
-                if (a.rowss != nullptr) {  // the two half-waves hold the two halves of this token's 128-column run
-                    ss += __shfl_xor(ss, 32, WAVE);
-                    if (half == 0) a.rowss[(size_t)m * (a.N / 128) + (n0 + wn * 128) / 128] = ss;
-                }
-            }
-        }
+    for (int i = 0; i < 4; ++i) {
+        vx[i] = (uint32_t)(m0 + i * 64 + ld_r) * (uint32_t)a.ldx * 2u + (uint32_t)ld_c * 16u;
+        vw[i] = (uint32_t)(n0 + i * 64 + ld_r) * (uint32_t)a.K * 2u + (uint32_t)ld_c * 16u;
     }
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    auto issue_stage = [&](int stage, int buf) {
+        const int koff = (st0 + stage) * (G2_BK * 2);
+        char* dst = smem + buf * G2_STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + i * 4096), 16, vx[i], koff, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + i * 4096), 16, vw[i], koff, 0, 0);
+    };
+
+    // fragment addresses (bytes from the start of a stage's X part); kk selects the 16-wide k-step inside the stage
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const uint32_t sw = (uint32_t)((l32 >> 2) & 3);
+    uint32_t ax[2], aw[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const uint32_t slot = ((uint32_t)(kk * 2 + half) ^ sw) * 16u;
+        ax[kk] = lds0 + (uint32_t)(wm * 128 + l32) * 64u + slot;
+        aw[kk] = lds0 + (uint32_t)G2_OP_BYTES + (uint32_t)(wn * 128 + l32) * 64u + slot;
+    }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 w0[4], x0[4], w1[4], x1[4];
+#define RS_READ_FRAGS(wf, xf, kk, bufoff)                                  \
+    do {                                                                   \
+        const uint32_t aw_ = aw[kk] + (bufoff), ax_ = ax[kk] + (bufoff);   \
+        RS_DS_READ_B128(wf[0], aw_, 0);                                    \
+        RS_DS_READ_B128(xf[0], ax_, 0);                                    \
+        RS_DS_READ_B128(wf[1], aw_, 2048);                                 \
+        RS_DS_READ_B128(xf[1], ax_, 2048);                                 \
+        RS_DS_READ_B128(wf[2], aw_, 4096);                                 \
+        RS_DS_READ_B128(xf[2], ax_, 4096);                                 \
+        RS_DS_READ_B128(wf[3], aw_, 6144);                                 \
+        RS_DS_READ_B128(xf[3], ax_, 6144);                                 \
+    } while (0)
+
+#ifdef RS_GEMM_TIMING
+    unsigned long long dbg_vm = 0, dbg_bar = 0, dbg_first = 0, dbg_last = 0, dbg_start;
+    asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_start));
+#endif
+    issue_stage(0, 0);
+    issue_stage(min(1, ns - 1), 1);
+    issue_stage(min(2, ns - 1), 2);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    asm volatile("s_barrier" ::: "memory");
+    RS_READ_FRAGS(w0, x0, 0, 0u);
+
+#define RS_MFMA(wf, xf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0)
+#define RS_FENCE() __builtin_amdgcn_sched_barrier(0)
+    for (int s = 0; s < ns; ++s) {
+        const uint32_t bufoff = (uint32_t)(s & 3) * G2_STAGE_BYTES;
+        const uint32_t nextoff = (uint32_t)((s + 1) & 3) * G2_STAGE_BYTES;
+        // ---- first half: 16 MFMAs on the kk=0 fragments; one memory instruction rides behind each MFMA so that its
+        //      issue latency (LDS queue, texture-address queue) overlaps the matrix pipe instead of stalling it
+        const int koff = (st0 + min(s + 3, ns - 1)) * (G2_BK * 2);
+        char* dst = smem + ((s + 3) & 3) * G2_STAGE_BYTES + wave * 1024;
+        const uint32_t aw1 = aw[1] + bufoff, ax1 = ax[1] + bufoff;
+        tie_wait_lgkm0(w0, x0);
+        RS_MFMA(w0, x0, 0, 0); RS_DS_READ_B128(w1[0], aw1, 0);    RS_FENCE();
+        RS_MFMA(w0, x0, 0, 1); RS_DS_READ_B128(x1[0], ax1, 0);    RS_FENCE();
+        RS_MFMA(w0, x0, 0, 2); RS_DS_READ_B128(w1[1], aw1, 2048); RS_FENCE();
+        RS_MFMA(w0, x0, 0, 3); RS_DS_READ_B128(x1[1], ax1, 2048); RS_FENCE();
+        RS_MFMA(w0, x0, 1, 0); RS_DS_READ_B128(w1[2], aw1, 4096); RS_FENCE();
+        RS_MFMA(w0, x0, 1, 1); RS_DS_READ_B128(x1[2], ax1, 4096); RS_FENCE();
+        RS_MFMA(w0, x0, 1, 2); RS_DS_READ_B128(w1[3], aw1, 6144); RS_FENCE();
+        RS_MFMA(w0, x0, 1, 3); RS_DS_READ_B128(x1[3], ax1, 6144); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 0); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst), 16, vx[0], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 1); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 4096), 16, vx[1], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 2); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 8192), 16, vx[2], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 3); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 12288), 16, vx[3], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 0); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES), 16, vw[0], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 1); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 4096), 16, vw[1], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 2); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 8192), 16, vw[2], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 3); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 12288), 16, vw[3], koff, 0, 0); RS_FENCE();
+        tie_wait_lgkm0(w1, x1);  // every LDS read of this stage has landed before the barrier frees its buffer
+#ifdef RS_GEMM_TIMING
+        unsigned long long t0_, t1_, t2_;
+        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t0_));
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t1_));
+        asm volatile("s_barrier" ::: "memory");
+        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t2_));
+        dbg_vm += t1_ - t0_; dbg_bar += t2_ - t1_;
+        if (s == 0) dbg_first = t2_;
+        dbg_last = t2_;
+#else
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+#endif
+        RS_FENCE();
+        // ---- second half: 16 MFMAs on the kk=1 fragments; the next stage's kk=0 fragments are fetched behind the first 8
+        const uint32_t aw0 = aw[0] + nextoff, ax0 = ax[0] + nextoff;
+        RS_MFMA(w1, x1, 0, 0); RS_DS_READ_B128(w0[0], aw0, 0);    RS_FENCE();
+        RS_MFMA(w1, x1, 0, 1); RS_DS_READ_B128(x0[0], ax0, 0);    RS_FENCE();
+        RS_MFMA(w1, x1, 0, 2); RS_DS_READ_B128(x0[1], ax0, 2048); RS_FENCE();
+        RS_MFMA(w1, x1, 0, 3); RS_DS_READ_B128(x0[2], ax0, 4096); RS_FENCE();
+        RS_MFMA(w1, x1, 1, 0); RS_DS_READ_B128(x0[3], ax0, 6144); RS_FENCE();
+        RS_MFMA(w1, x1, 1, 1); RS_DS_READ_B128(w0[1], aw0, 2048); RS_FENCE();
+        RS_MFMA(w1, x1, 1, 2); RS_DS_READ_B128(w0[2], aw0, 4096); RS_FENCE();
+        RS_MFMA(w1, x1, 1, 3); RS_DS_READ_B128(w0[3], aw0, 6144); RS_FENCE();
+        RS_MFMA(w1, x1, 2, 0); RS_MFMA(w1, x1, 2, 1); RS_MFMA(w1, x1, 2, 2); RS_MFMA(w1, x1, 2, 3);
+        RS_MFMA(w1, x1, 3, 0); RS_MFMA(w1, x1, 3, 1); RS_MFMA(w1, x1, 3, 2); RS_MFMA(w1, x1, 3, 3);
+        RS_FENCE();
+    }
+#undef RS_MFMA
+#undef RS_FENCE
+    tie_wait_lgkm0(w0, x0);  // the look-ahead read of the stage after the last one
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef RS_READ_FRAGS
+#ifdef RS_GEMM_TIMING
+    if (lane == 0) {
+        unsigned long long* d = a.dbg + ((size_t)blockIdx.x * 4 + wave) * 4;
+        d[0] = dbg_vm; d[1] = dbg_bar; d[2] = dbg_last - dbg_first; d[3] = ns - 1;
+    }
+#endif
+
+    gemm_epilogue<EPI>(a, acc, m0, n0, wm, wn, half, l32, split);
+#ifdef RS_GEMM_TIMING
+    if (tid == 0) {
+        unsigned long long dbg_end;
+        asm volatile("s_waitcnt vmcnt(0)\n s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_end));
+        unsigned long long* d = a.dbg + (size_t)gridDim.x * 16 + (size_t)blockIdx.x * 2;
+        d[0] = dbg_start; d[1] = dbg_end;
+    }
+#endif
 }
 
 // Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).

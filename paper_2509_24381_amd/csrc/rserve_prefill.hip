@@ -42,6 +42,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int RING_SLOTS = 32;
+int g_gemm_variant = 1;  // 1: DMA-pipelined kernel, 0: register-staged kernel (RS_GEMM environment variable)
 
 }  // namespace
 
@@ -135,7 +136,10 @@ rs_status launch_gemm(GemmArgs a, int splits, hipStream_t st) {
     const int slabs = a.K / GEMM_BK;
     a.k_slabs_per_split = (slabs + splits - 1) / splits;
     dim3 grid(a.tiles_m * a.tiles_n, splits);
-    hipLaunchKernelGGL(gemm_bf16_256x256_kernel<EPI>, grid, dim3(256), GEMM_LDS_BYTES, st, a);
+    if (g_gemm_variant == 1)
+        hipLaunchKernelGGL(gemm_bf16_dma_kernel<EPI>, grid, dim3(256), G2_LDS_BYTES, st, a);
+    else
+        hipLaunchKernelGGL(gemm_bf16_256x256_kernel<EPI>, grid, dim3(256), GEMM_LDS_BYTES, st, a);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -393,6 +397,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->cfg = f;
     c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
+    if (const char* e = getenv("RS_GEMM")) g_gemm_variant = atoi(e);
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
     c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;
@@ -430,6 +435,10 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_QKV_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
