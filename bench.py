@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# Bytes crossing the L2 / fabric boundary per gate/up GEMM launch at T=2048 on the 7B shape, from the two rocprofv3 --pmc
+# passes summarised in profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
+# factors a plain copy kernel of known size gives).  Algorithmic bytes of the same launch: 363.9e6.
+GATE_UP_TRAFFIC_BYTES = (460235.0 * 2.0 + 75854.5 * 1.0) * 1024
 
 
 def cpu_baseline(wl, w0, x, rows: int):
@@ -56,6 +60,9 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, run one plain 256 MiB elementwise copy kernel (torch.mul(a, 1, out=b)); "
+                         "gives the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -117,9 +124,10 @@ def main():
                    "calls_per_step": calls_per_step, "shape": "hidden 3584, 28 q / 4 kv heads, head_dim 128, mlp 18944"},
         "tflops": tflops,
         "mfma_frac_whole_path": tflops / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": "gemm_bf16_256x256_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
+        "roofline": {"kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
                      "bound": "mfma", "achieved": gu_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": GATE_UP_TRAFFIC_BYTES,
+                     "traffic_unit": "bytes per launch (L2/fabric boundary, rocprofv3 --pmc)", "algorithmic_bytes": 363.9e6,
                      "avg_ms": gu_avg_ms, "launches": gu_n},
     }
 
@@ -133,6 +141,14 @@ def main():
             bd[name] = ms / max(n, 1)
         stack.ctx.profile_enable(None)
         out["breakdown_avg_ms_per_call"] = bd
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, w0, x, args.cpu_rows)
