@@ -177,7 +177,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
                 for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[mi][r]);
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, WAVE));
             const float m_new = fmaxf(m_run, mloc);          // finite: key 0 is visible to every query
-            const float alpha = exp2f((m_run - m_new) * scale_log2e);
+            // the accumulated output is rescaled only when some query of this wavefront saw its running max grow
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            }
             const float mb = m_new * scale_log2e;
             m_run = m_new;
             float psum = 0.0f;
@@ -186,15 +194,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = exp2f(s[mi][r] * scale_log2e - mb);
+                    // raw v_exp_f32: arguments are <= 0, results below the normal range may flush to zero
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mi][r], scale_log2e, -mb));
                     psum += p;
                     pf[mi * 2 + (r >> 3)][r & 7] = f32_to_bf16(p);
                 }
-            l_run = l_run * alpha + psum;
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            l_run += psum;
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
                 const uint32_t vrow = (uint32_t)(t * 32 + l32) * 128u;

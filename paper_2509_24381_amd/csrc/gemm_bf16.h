@@ -56,7 +56,10 @@ constexpr int GEMM_BM = 256, GEMM_BN = 256, GEMM_BK = 64;
 constexpr int GEMM_STAGE_BYTES = GEMM_BM * GEMM_BK * 2;          // one operand, one slab: 32 KB
 constexpr int GEMM_LDS_BYTES = 4 * GEMM_STAGE_BYTES;             // 2 operands x 2 buffers
 
-RS_DEVICE float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
+// silu(g) = g / (1 + 2^(-g log2 e)) with the raw v_exp_f32 / v_rcp_f32 instructions (1 ulp each; the result is rounded to bf16)
+RS_DEVICE float silu_f32(float g) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
+}
 
 // Lane-local epilogue shared by the GEMM kernels.  acc[i][j][r] holds token m = m0 + wm*128 + j*32 + l32 and
 // feature n = n0 + wn*128 + i*32 + 8*(r>>2) + 4*half + (r&3).
@@ -297,7 +300,16 @@ constexpr int G2_OP_BYTES = 256 * G2_BK * 2;       // 16 KB
 constexpr int G2_STAGE_BYTES = 2 * G2_OP_BYTES;    // 32 KB
 constexpr int G2_LDS_BYTES = G2_STAGES * G2_STAGE_BYTES;
 
+#ifdef RS_EXP_NO_LDS
+#define RS_DS_READ_B128(dst, addr, off) asm volatile("" : "+v"(dst) : "v"(addr))
+#else
 #define RS_DS_READ_B128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
+#endif
+#ifdef RS_EXP_NO_DMA
+#define RS_DMA_LOAD(rsrc, dstp, voff, soff) asm volatile("" ::"v"(voff), "s"(soff))
+#else
+#define RS_DMA_LOAD(rsrc, dstp, voff, soff) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dstp), 16, voff, soff, 0, 0)
+#endif
 
 RS_DEVICE void tie_wait_lgkm8(bf16x8 (&w)[4], bf16x8 (&x)[4]) {
     asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
@@ -419,14 +431,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(GemmArgs a) {
         RS_MFMA(w0, x0, 1, 1); RS_DS_READ_B128(x1[2], ax1, 4096); RS_FENCE();
         RS_MFMA(w0, x0, 1, 2); RS_DS_READ_B128(w1[3], aw1, 6144); RS_FENCE();
         RS_MFMA(w0, x0, 1, 3); RS_DS_READ_B128(x1[3], ax1, 6144); RS_FENCE();
-        RS_MFMA(w0, x0, 2, 0); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst), 16, vx[0], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 2, 1); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 4096), 16, vx[1], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 2, 2); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 8192), 16, vx[2], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 2, 3); __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(dst + 12288), 16, vx[3], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 3, 0); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES), 16, vw[0], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 3, 1); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 4096), 16, vw[1], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 3, 2); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 8192), 16, vw[2], koff, 0, 0); RS_FENCE();
-        RS_MFMA(w0, x0, 3, 3); __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(dst + G2_OP_BYTES + 12288), 16, vw[3], koff, 0, 0); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 0); RS_DMA_LOAD(rx, dst, vx[0], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 1); RS_DMA_LOAD(rx, dst + 4096, vx[1], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 2); RS_DMA_LOAD(rx, dst + 8192, vx[2], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 2, 3); RS_DMA_LOAD(rx, dst + 12288, vx[3], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 0); RS_DMA_LOAD(rw, dst + G2_OP_BYTES, vw[0], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 1); RS_DMA_LOAD(rw, dst + G2_OP_BYTES + 4096, vw[1], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 2); RS_DMA_LOAD(rw, dst + G2_OP_BYTES + 8192, vw[2], koff); RS_FENCE();
+        RS_MFMA(w0, x0, 3, 3); RS_DMA_LOAD(rw, dst + G2_OP_BYTES + 12288, vw[3], koff); RS_FENCE();
         tie_wait_lgkm0(w1, x1);  // every LDS read of this stage has landed before the barrier frees its buffer
 #ifdef RS_GEMM_TIMING
         unsigned long long t0_, t1_, t2_;
