@@ -300,16 +300,8 @@ constexpr int G2_OP_BYTES = 256 * G2_BK * 2;       // 16 KB
 constexpr int G2_STAGE_BYTES = 2 * G2_OP_BYTES;    // 32 KB
 constexpr int G2_LDS_BYTES = G2_STAGES * G2_STAGE_BYTES;
 
-#ifdef RS_EXP_NO_LDS
-#define RS_DS_READ_B128(dst, addr, off) asm volatile("" : "+v"(dst) : "v"(addr))
-#else
 #define RS_DS_READ_B128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
-#endif
-#ifdef RS_EXP_NO_DMA
-#define RS_DMA_LOAD(rsrc, dstp, voff, soff) asm volatile("" ::"v"(voff), "s"(soff))
-#else
 #define RS_DMA_LOAD(rsrc, dstp, voff, soff) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dstp), 16, voff, soff, 0, 0)
-#endif
 
 RS_DEVICE void tie_wait_lgkm8(bf16x8 (&w)[4], bf16x8 (&x)[4]) {
     asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
