@@ -1,0 +1,186 @@
+"""GPU edge cases of the C ABI: limits, aliasing, poisoned buffers, cache bookkeeping, both kernel variants."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import ChunkedPrefill, LayerParams, layer_forward, prefill_batch, rel_fro
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def R():
+    from paper_2509_24381_amd import runner
+    return runner
+
+
+def check(name, got, want, tol=TOL):
+    err = rel_fro(got, want)
+    print(f"[parity] {name}: rel_fro = {err:.3e}", flush=True)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    assert err <= tol, f"{name}: rel_fro {err:.3e} > {tol}"
+
+
+def test_poisoned_buffers_exact_capacity_and_in_place_output():
+    """KV slab and workspace start as NaN bit patterns; the chunk sizes end exactly at capacity; y aliases x.
+
+    Nothing the kernels read may depend on uninitialised memory (the V cache's zero tail is maintained by the append
+    kernel), the cache must hold exactly `capacity` tokens, and writing the output over the input must be safe."""
+    r = R()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 5, gains="uniform")
+    n = 192                                   # capacity is a multiple of 64: the cache is filled to its last slot
+    x = synth.prompt_rows([("image", 100), ("text", 92)], shape.hidden, 6)
+    stack = r.LayerStack(shape, [w], max_tokens=100, max_requests=2, max_pos=n)
+    kv = stack.new_cache(n)
+    assert kv.capacity == n
+    kv.slab.view(torch.int16).fill_(0x7FC1)      # bf16 NaN pattern everywhere
+    stack.ws.view(torch.int16).fill_(0x7FC1)
+    xd = r.to_device_bf16(x)
+    buf = xd.clone()
+    for a, b in [(0, 100), (100, 133), (133, 192)]:
+        stack.ctx.prefill_chunk(stack.layers[0], 0, kv, buf[a:b], buf[a:b], stack.ws)   # in place
+    torch.cuda.synchronize()
+    assert kv.length(0) == n
+    y_ref, k_ref, v_ref = layer_forward(x, LayerParams.from_arrays(shape, w))
+    k, v = kv.export(0)
+    check("poisoned Y (in place)", r.to_numpy_f32(buf), y_ref)
+    check("poisoned K", r.to_numpy_f32(k), k_ref)
+    check("poisoned V", r.to_numpy_f32(v), v_ref)
+    # one more row does not fit
+    from paper_2509_24381_amd.binding import RsError
+    with pytest.raises(RsError) as e:
+        stack.ctx.prefill_chunk(stack.layers[0], 0, kv, xd[:1], buf[:1], stack.ws)
+    assert e.value.status_name == "RS_ECAPACITY" and kv.length(0) == n
+
+
+def test_truncate_then_refill_matches_fresh_prefill():
+    """Dropping the newest tokens and prefilling them again reproduces the cache and the output bit for bit."""
+    r = R()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 8)
+    x = synth.prompt_rows([("text", 70), ("image", 90)], shape.hidden, 9)
+    stack = r.LayerStack(shape, [w], max_tokens=160, max_requests=1, max_pos=256)
+    kv = stack.new_cache(200)
+    xd = r.to_device_bf16(x)
+    y1 = torch.empty_like(xd)
+    stack.ctx.prefill_chunk(stack.layers[0], 0, kv, xd[:100], y1[:100], stack.ws)
+    stack.ctx.prefill_chunk(stack.layers[0], 0, kv, xd[100:], y1[100:], stack.ws)
+    torch.cuda.synchronize()
+    k1, v1 = kv.export(0)
+    kv.truncate(0, 100)
+    assert kv.length(0) == 100
+    y2 = torch.empty_like(xd[100:])
+    stack.ctx.prefill_chunk(stack.layers[0], 0, kv, xd[100:], y2, stack.ws)
+    torch.cuda.synchronize()
+    k2, v2 = kv.export(0)
+    assert torch.equal(y2, y1[100:]) and torch.equal(k1, k2) and torch.equal(v1, v2)
+    kv.reset()
+    assert kv.length(0) == 0
+
+
+def test_single_rows_against_long_prefix_and_full_budget_call():
+    """T = 1 calls (the smallest legal chunk) against a growing prefix, then one call that uses the whole token budget."""
+    r = R()
+    shape = synth.LayerShape("s", 256, 8, 2, 64, 512)
+    w = synth.layer_weights(shape, 12, qkv_bias=True, gains="uniform")
+    n = 700
+    x = synth.prompt_rows([("image", 300), ("text", 400)], shape.hidden, 13)
+    stack = r.LayerStack(shape, [w], max_tokens=512, max_requests=1, max_pos=1024, qkv_bias=True)
+    kv = stack.new_cache(n)
+    xd = r.to_device_bf16(x)
+    y = torch.empty_like(xd)
+    chunks = [(0, 183)] + [(i, i + 1) for i in range(183, 188)] + [(188, 700)]    # 512 = the whole budget
+    for a, b in chunks:
+        stack.ctx.prefill_chunk(stack.layers[0], 0, kv, xd[a:b], y[a:b], stack.ws)
+    torch.cuda.synchronize()
+    y_ref, k_ref, v_ref = layer_forward(x, LayerParams.from_arrays(shape, w))
+    k, v = kv.export(0)
+    check("T=1 / full budget Y", r.to_numpy_f32(y), y_ref)
+    check("T=1 rows only", r.to_numpy_f32(y)[183:188], y_ref[183:188])
+    check("T=1 / full budget K", r.to_numpy_f32(k), k_ref)
+    check("T=1 / full budget V", r.to_numpy_f32(v), v_ref)
+
+
+def test_batch_at_request_limit_with_mixed_capacities_is_order_equivariant():
+    """R = max_requests, caches of different capacities, permuting the requests permutes the output blocks only."""
+    r = R()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 21)
+    rng = np.random.default_rng(22)
+    n_req = 8
+    priors = [0, 7, 64, 65, 127, 128, 200, 31]
+    lens = [9, 1, 30, 2, 17, 64, 3, 2]
+    caps = [64, 64, 128, 128, 192, 192, 256, 64]
+    reqs = []
+    for p, t in zip(priors, lens):
+        pk = synth.bf16_round(rng.standard_normal((p, 2, 64), dtype=np.float32))
+        pv = synth.bf16_round(rng.standard_normal((p, 2, 64), dtype=np.float32))
+        rows = synth.bf16_round(rng.standard_normal((t, 256), dtype=np.float32))
+        reqs.append(synth.BatchRequest(p, pk, pv, rows))
+    stack = r.LayerStack(shape, [w], max_tokens=sum(lens), max_requests=n_req, max_pos=256)
+
+    def run(order):
+        kvs = []
+        for i in order:
+            kv = stack.new_cache(caps[i])
+            if reqs[i].prior_len:
+                kv.import_(0, r.to_device_bf16(reqs[i].prior_k), r.to_device_bf16(reqs[i].prior_v))
+            kvs.append(kv)
+        x = np.concatenate([reqs[i].rows for i in order])
+        y = stack.prefill_batch(0, kvs, [lens[i] for i in order], r.to_device_bf16(x))
+        torch.cuda.synchronize()
+        return r.to_numpy_f32(y), [tuple(r.to_numpy_f32(t_) for t_ in kv.export(0)) for kv in kvs]
+
+    order = list(range(n_req))
+    y, caches = run(order)
+    p = LayerParams.from_arrays(shape, w)
+    states = [ChunkedPrefill(p, q.prior_k, q.prior_v) for q in reqs]
+    y_ref = prefill_batch(states, [q.rows for q in reqs])
+    check("limit batch Y", y, y_ref)
+    for i, st in enumerate(states):
+        check(f"limit batch K req {i}", caches[i][0], st.k)
+        check(f"limit batch V req {i}", caches[i][1], st.v)
+    perm = [5, 0, 7, 2, 6, 1, 4, 3]
+    yp, caches_p = run(perm)
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    off = 0
+    for slot, i in enumerate(perm):
+        np.testing.assert_array_equal(yp[off: off + lens[i]], y[starts[i]: starts[i] + lens[i]])
+        np.testing.assert_array_equal(caches_p[slot][0], caches[i][0])
+        np.testing.assert_array_equal(caches_p[slot][1], caches[i][1])
+        off += lens[i]
+
+
+def test_export_import_round_trip_is_bit_exact():
+    r = R()
+    shape = synth.LayerShape("s128", 256, 2, 1, 128, 256)
+    w = synth.layer_weights(shape, 30)
+    stack = r.LayerStack(shape, [w, w], max_tokens=64, max_requests=1, max_pos=512)
+    rng = np.random.default_rng(31)
+    for n in (1, 63, 64, 65, 300):
+        k = synth.bf16_round(rng.standard_normal((n, 1, 128), dtype=np.float32))
+        v = synth.bf16_round(rng.standard_normal((n, 1, 128), dtype=np.float32))
+        kv = stack.new_cache(320)
+        kv.import_(1, r.to_device_bf16(k), r.to_device_bf16(v))
+        assert kv.length(1) == n and kv.length(0) == 0
+        k2, v2 = kv.export(1)
+        np.testing.assert_array_equal(r.to_numpy_f32(k2), k)
+        np.testing.assert_array_equal(r.to_numpy_f32(v2), v)
+
+
+@pytest.mark.parametrize("env", [{"RS_GEMM": "0"}, {"RS_SPLITK": "1"}, {"RS_SPLITK": "3"}])
+def test_alternative_kernel_paths_meet_the_same_bar(env):
+    """The register-staged GEMM and other split-K factors are selectable by environment variable; each must pass the
+    workload-1 parity test on its own (run in a child process because the choice is read once per process)."""
+    child_env = dict(os.environ, **env)
+    proc = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", os.path.join(ROOT, "tests", "test_gpu_parity.py"),
+                           "-k", "workload1 or small_ragged or two_layers"],
+                          cwd=ROOT, env=child_env, capture_output=True, text=True, timeout=600)
+    assert proc.returncode == 0, proc.stdout[-2000:] + proc.stderr[-2000:]
