@@ -30,9 +30,11 @@ HBM_PEAK_GBS = 8000.0
 GATE_UP_TRAFFIC_BYTES = (460235.0 * 2.0 + 75854.5 * 1.0) * 1024
 
 
-def cpu_baseline(wl, w0, x, rows: int):
-    """The oracle as it stands, one layer over the first `rows` rows of the same prompt, on the host cores."""
-    import numpy as np
+def cpu_baseline(wl, w0, x, target_seconds: float):
+    """The oracle as it stands, one layer over the first rows of the same prompt, on the host cores.
+
+    A 512-row probe estimates the host's speed; the reported sample is then sized for about `target_seconds` of CPU
+    work (at most the whole prompt through layer 0)."""
     from oracle import LayerParams, layer_forward
     threads = os.cpu_count() or 1
     try:
@@ -43,13 +45,24 @@ def cpu_baseline(wl, w0, x, rows: int):
     except Exception:
         pass
     p = LayerParams.from_arrays(wl.shape, w0)
-    t0 = time.perf_counter()
-    layer_forward(x[:rows], p)
-    dt = time.perf_counter() - t0
-    flops = wl.shape.linear_flops_per_token() * rows + wl.shape.attn_flops(rows, 0)
+
+    def flops(rows):
+        return wl.shape.linear_flops_per_token() * rows + wl.shape.attn_flops(rows, 0)
+
+    def run(rows):
+        t0 = time.perf_counter()
+        layer_forward(x[:rows], p)
+        return time.perf_counter() - t0
+
+    probe_rows = min(512, x.shape[0])
+    rate = flops(probe_rows) / run(probe_rows)
+    rows = probe_rows
+    while rows < x.shape[0] and flops(min(2 * rows, x.shape[0])) / rate <= target_seconds:
+        rows = min(2 * rows, x.shape[0])
+    dt = run(rows)
     return {"value": rows / dt, "unit": "layer-tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"fp64 oracle layer_forward, layer 0, first {rows} rows of the same prompt (P=0), {dt:.2f} s, "
-                      f"{flops / dt / 1e9:.1f} GFLOP/s"}
+                      f"{flops(rows) / dt / 1e9:.1f} GFLOP/s"}
 
 
 def main():
@@ -59,7 +72,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline sample is sized for")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain 256 MiB elementwise copy kernel (torch.mul(a, 1, out=b)); "
                          "gives the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs a kernel of known traffic to scale by")
@@ -151,7 +164,7 @@ def main():
         del src, dst
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, w0, x, args.cpu_rows)
+        out["cpu_baseline"] = cpu_baseline(wl, w0, x, args.cpu_seconds)
     print(json.dumps(out), flush=True)
 
 
