@@ -73,15 +73,23 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const bf16* __restrict__
 
 // ---------------------------------------------------------------- weight packing (one-time)
 // dst[prow][k] = bf16(src[srow][k] * gain[k]): the RMSNorm gain is folded into the weight columns of the GEMM that follows
-// the norm.  interleave_I = 0: srow = prow.  interleave_I = I > 0 (gate/up): packed row (b*64 + r) = gate row (b*32 + r),
-// packed row (b*64 + 32 + r) = up row (b*32 + r), so that a wavefront's MFMA tiles alternate gate, up, gate, up.
+// the norm, and rows are reordered so that what an epilogue combines sits in one 32-row unit (one MFMA tile), in rows t and
+// t + 16, which one lane holds:
+//   PACK_GATE_UP (p0 = I):  unit u = 16 gate rows 16u..16u+15, then the up rows I + 16u..
+//   PACK_QKV_ROPE (p0 = head_dim, p1 = number of q and k rows): unit u of a head = features 16u..16u+15 of the head's
+//                 first half, then their rotate-half partners head_dim/2 + 16u..; v rows keep their order
+enum PackMode { PACK_IDENTITY = 0, PACK_GATE_UP = 1, PACK_QKV_ROPE = 2 };
 __global__ __launch_bounds__(256) void pack_rows_kernel(const bf16* __restrict__ src, const bf16* __restrict__ gain,
-                                                        bf16* __restrict__ dst, int K, int interleave_I) {
+                                                        bf16* __restrict__ dst, int K, int mode, int p0, int p1) {
     const int prow = blockIdx.x;
     int srow = prow;
-    if (interleave_I > 0) {
-        const int b = prow >> 6, r = prow & 63;
-        srow = (r < 32) ? (b * 32 + r) : (interleave_I + b * 32 + (r - 32));
+    const int t = prow & 31;
+    if (mode == PACK_GATE_UP) {
+        const int u = prow >> 5;
+        srow = (t < 16) ? (u * 16 + t) : (p0 + u * 16 + (t - 16));
+    } else if (mode == PACK_QKV_ROPE && prow < p1) {
+        const int head = prow / p0, uh = (prow % p0) >> 5;
+        srow = head * p0 + ((t < 16) ? (uh * 16 + t) : (p0 / 2 + uh * 16 + (t - 16)));
     }
     const bf16* s = src + (size_t)srow * K;
     bf16* d = dst + (size_t)prow * K;

@@ -16,7 +16,7 @@
 #include "attention.h"
 #include "common.h"
 #include "elementwise.h"
-#include "gemm_bf16.h"
+#include "gemm_strip.h"
 
 namespace {
 
@@ -42,7 +42,6 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int RING_SLOTS = 32;
-int g_gemm_variant = 1;  // 1: DMA-pipelined kernel, 0: register-staged kernel (RS_GEMM environment variable)
 
 }  // namespace
 
@@ -57,6 +56,7 @@ struct rs_ctx {
     size_t slot_bytes = 0;
     int next_slot = 0;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
+    int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
     // measurement hook: HIP events around every launch of one step of the layer
     int prof_step = -1;
@@ -94,16 +94,22 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     return d;
 }
 
-int choose_splitk(const rs_ctx* c, int tiles, int k_slabs) {
-    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_slabs));
-    // one 256x256 tile per CU: split K when less than ~60% of the 256 CUs would have a tile
+// Strips per 256-row block of a GEMM with `units` 32-feature units: one workgroup per compute unit when there is enough
+// width, never more strips than units.
+int strips_for(const rs_ctx* c, int tiles_m, int splits, int units) {
+    return std::max(1, std::min(units, c->n_cu / std::max(1, tiles_m * splits)));
+}
+
+int choose_splitk(const rs_ctx* c, int tiles_m, int units, int k_stages) {
+    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_stages));
+    // split K only while the unsplit launch cannot give every compute unit a strip
     int s = 1;
-    while (s < 4 && tiles * (s + 1) <= 256 && k_slabs / (s + 1) >= 8) ++s;
+    while (s < 4 && tiles_m * std::min(units, c->n_cu / std::max(1, tiles_m)) * (s + 1) <= c->n_cu && k_stages / (s + 1) >= 16) ++s;
     return s;
 }
 
 struct WorkspaceLayout {
-    size_t qkv, attn, r, act, partial, inv_rms1, inv_rms2, rowss, desc, total;
+    size_t qkv, attn, r, act, partial, inv_rms1, inv_rms2, desc, total;
 };
 
 WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
@@ -123,47 +129,45 @@ WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
     w.partial = take(4 * t * f.hidden * 4);  // up to 4 split-K partial planes of [T, H] fp32
     w.inv_rms1 = take(t * 4);
     w.inv_rms2 = take(t * 4);
-    w.rowss = take(t * (f.hidden / 128) * 4);
     w.desc = take(desc_sizes(c, T, R).total);
     w.total = off;
     return w;
 }
 
 template <int EPI>
-rs_status launch_gemm(GemmArgs a, int splits, hipStream_t st) {
-    a.tiles_m = (a.M + GEMM_BM - 1) / GEMM_BM;
-    a.tiles_n = a.N / GEMM_BN;
-    const int slabs = a.K / GEMM_BK;
-    a.k_slabs_per_split = (slabs + splits - 1) / splits;
-    dim3 grid(a.tiles_m * a.tiles_n, splits);
-    if (g_gemm_variant == 1)
-        hipLaunchKernelGGL(gemm_bf16_dma_kernel<EPI>, grid, dim3(256), G2_LDS_BYTES, st, a);
-    else
-        hipLaunchKernelGGL(gemm_bf16_256x256_kernel<EPI>, grid, dim3(256), GEMM_LDS_BYTES, st, a);
+rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
+    a.tiles_m = (a.M + GS_BM - 1) / GS_BM;
+    a.strips = strips_for(c, a.tiles_m, splits, a.N / 32);
+    const int stages = a.K / GS_BK;
+    a.stages_per_split = (stages + splits - 1) / splits;
+    splits = (stages + a.stages_per_split - 1) / a.stages_per_split;  // no empty K range
+    dim3 grid(a.tiles_m * a.strips, splits);
+    hipLaunchKernelGGL(gemm_strip_kernel<EPI>, grid, dim3(256), GS_LDS_BYTES, st, a);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
 
-// out = resid + X W^T, through split-K partials when that fills the machine better.  When inv_rms_out is given it
-// receives rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input); rowss is scratch for it.
+// out = resid + X W^T, through split-K partials when the unsplit launch would leave compute units idle.  When inv_rms_out
+// is given it receives rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input).
 rs_status gemm_residual(const rs_ctx* c, const bf16* X, int ldx, const bf16* W, const bf16* resid, bf16* out,
-                        int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, hipStream_t st) {
+                        int M, int N, int K, float* partial, float* inv_rms_out, hipStream_t st) {
     GemmArgs a{};
     a.X = X; a.ldx = ldx; a.W = W; a.out = out; a.ldo = N; a.resid = resid; a.ldr = N; a.partial = partial;
     a.M = M; a.N = N; a.K = K;
     const float eps = c->cfg.rms_eps;
-    const int tiles = ((M + GEMM_BM - 1) / GEMM_BM) * (N / GEMM_BN);
-    const int splits = choose_splitk(c, tiles, K / GEMM_BK);
+    int splits = choose_splitk(c, (M + GS_BM - 1) / GS_BM, N / 32, K / GS_BK);
+    if (splits > 1) {
+        const int sps = (K / GS_BK + splits - 1) / splits;
+        splits = (K / GS_BK + sps - 1) / sps;
+    }
     if (splits == 1) {
-        a.rowss = inv_rms_out ? rowss : nullptr;
-        rs_status s = launch_gemm<EPI_RESIDUAL>(a, 1, st);
+        rs_status s = launch_gemm<EPI_RESIDUAL>(c, a, 1, st);
         if (s != RS_OK || !inv_rms_out) return s;
-        hipLaunchKernelGGL(rowss_finalize_kernel, dim3((M + 255) / 256), dim3(256), 0, st, (const float*)rowss, N / 128, M, N,
-                           eps, inv_rms_out);
+        hipLaunchKernelGGL(row_inv_rms_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const bf16*)out, inv_rms_out, M, N, eps);
         RS_HIP(hipGetLastError());
         return RS_OK;
     }
-    rs_status s = launch_gemm<EPI_PARTIAL>(a, splits, st);
+    rs_status s = launch_gemm<EPI_PARTIAL>(c, a, splits, st);
     if (s != RS_OK) return s;
     hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)partial, splits, resid, N,
                        out, N, M, N, inv_rms_out, eps);
@@ -311,7 +315,6 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     float* partial = reinterpret_cast<float*>(wsb + L.partial);
     float* inv_rms1 = reinterpret_cast<float*>(wsb + L.inv_rms1);
     float* inv_rms2 = reinterpret_cast<float*>(wsb + L.inv_rms2);
-    float* rowss = reinterpret_cast<float*>(wsb + L.rowss);
     const bf16* xb = reinterpret_cast<const bf16*>(x);
     bf16* yb = reinterpret_cast<bf16*>(y);
     const int H = f.hidden, I = f.mlp_inter;
@@ -332,7 +335,7 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
         a.row_scale = inv_rms1; a.row_pos = d_rowpos; a.rope_cs = (const float2*)ctx->rope_dev;
         a.rope_cols = ctx->q_dim + ctx->kv_dim; a.head_dim = f.head_dim;
         a.M = T; a.N = ctx->qkv_dim; a.K = H;
-        if ((s = launch_gemm<EPI_QKV_ROPE>(a, 1, st)) != RS_OK) return s;
+        if ((s = launch_gemm<EPI_QKV_ROPE>(ctx, a, 1, st)) != RS_OK) return s;
     }
     tm.end(RS_STEP_QKV_GEMM);
     // cache append, attention
@@ -343,7 +346,7 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
-    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, inv_rms2, rowss, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, inv_rms2, st)) != RS_OK) return s;
     tm.end(RS_STEP_O_GEMM);
     // act = silu((r Wg'^T) / rms) * ((r Wu'^T) / rms)
     tm.begin(RS_STEP_GATE_UP_GEMM);
@@ -352,12 +355,12 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
         a.X = r; a.ldx = H; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I;
         a.row_scale = inv_rms2;
         a.M = T; a.N = 2 * I; a.K = H;
-        if ((s = launch_gemm<EPI_SWIGLU>(a, 1, st)) != RS_OK) return s;
+        if ((s = launch_gemm<EPI_SWIGLU>(ctx, a, 1, st)) != RS_OK) return s;
     }
     tm.end(RS_STEP_GATE_UP_GEMM);
     // y = r + act Wd^T
     tm.begin(RS_STEP_DOWN_GEMM);
-    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, nullptr, nullptr, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, nullptr, st)) != RS_OK) return s;
     tm.end(RS_STEP_DOWN_GEMM);
 
     for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
@@ -382,13 +385,13 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (f.head_dim != 64 && f.head_dim != 128) return fail(RS_EINVAL, "head_dim must be 64 or 128");
     if (f.n_q_heads % f.n_kv_heads) return fail(RS_EINVAL, "n_kv_heads must divide n_q_heads");
     const int q_dim = f.n_q_heads * f.head_dim, kv_dim = f.n_kv_heads * f.head_dim, qkv_dim = q_dim + 2 * kv_dim;
-    if (f.hidden % 256) return fail(RS_EINVAL, "hidden must be a multiple of 256");
-    if (qkv_dim % 256) return fail(RS_EINVAL, "(Hq + 2 Hkv) * head_dim must be a multiple of 256");
-    if (f.mlp_inter % 128) return fail(RS_EINVAL, "mlp_inter must be a multiple of 128");
-    if (q_dim % 128 || kv_dim % 128) return fail(RS_EINVAL, "Hq * head_dim and Hkv * head_dim must be multiples of 128");
+    if (f.hidden % 64) return fail(RS_EINVAL, "hidden must be a multiple of 64");
+    if (f.mlp_inter % 64) return fail(RS_EINVAL, "mlp_inter must be a multiple of 64");
     if (!(f.rms_eps >= 0.0f) || !(f.rope_theta > 0.0f)) return fail(RS_EINVAL, "rms_eps / rope_theta out of range");
     if ((size_t)f.max_tokens_per_call * (size_t)std::max(qkv_dim, f.mlp_inter) * 2 >= (size_t)1 << 31)
         return fail(RS_EINVAL, "max_tokens_per_call too large for 32-bit row offsets");
+    if ((size_t)f.max_tokens_per_call * (size_t)f.hidden * 4 >= (size_t)1 << 31)
+        return fail(RS_EINVAL, "max_tokens_per_call * hidden too large for 32-bit offsets into a split-K plane");
     if ((size_t)std::max(2 * f.mlp_inter, qkv_dim) * (size_t)f.hidden * 2 >= (size_t)1 << 31 ||
         (size_t)f.hidden * (size_t)f.mlp_inter * 2 >= (size_t)1 << 31)
         return fail(RS_EINVAL, "weight matrix too large for 32-bit row offsets");
@@ -397,7 +400,6 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->cfg = f;
     c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
-    if (const char* e = getenv("RS_GEMM")) g_gemm_variant = atoi(e);
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
     c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;
@@ -430,15 +432,18 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
         e = hipEventCreateWithFlags(&c->slot_done[i], hipEventDisableTiming);
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
     }
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0)
+        c->n_cu = n_cu;
+    if (const char* e = getenv("RS_NCU")) {  // test hook: fewer, wider strips exercise every tile width on small shapes
+        if (atoi(e) > 0) c->n_cu = atoi(e);
+    }
     // kernels that use more than 64 KB of LDS must opt in
-    e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_QKV_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_256x256_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_QKV_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, G2_LDS_BYTES);
+    e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_QKV_ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
@@ -498,7 +503,7 @@ rs_status rs_weights_pack(rs_ctx* c, const rs_layer_weights* src, void* dst, siz
     // W_qkv with the first norm's gain folded into its columns
     o.w_qkv = p;
     hipLaunchKernelGGL(pack_rows_kernel, dim3(c->qkv_dim), dim3(256), 0, st, (const bf16*)src->w_qkv, (const bf16*)src->ln1_g,
-                       reinterpret_cast<bf16*>(p), f.hidden, 0);
+                       reinterpret_cast<bf16*>(p), f.hidden, (int)PACK_QKV_ROPE, f.head_dim, c->q_dim + c->kv_dim);
     RS_HIP(hipGetLastError());
     p += align_up((size_t)c->qkv_dim * H * 2, 256);
     if (f.qkv_bias) {
@@ -507,10 +512,10 @@ rs_status rs_weights_pack(rs_ctx* c, const rs_layer_weights* src, void* dst, siz
         p += align_up((size_t)c->qkv_dim * 2, 256);
     }
     RS_HIP(copy(src->w_o, H * c->q_dim * 2, &o.w_o));
-    // W_gate / W_up interleaved in 32-row blocks, with the second norm's gain folded into their columns
+    // W_gate / W_up interleaved in 16-row blocks (one unit = 16 gate rows + their up rows), second norm gain folded in
     o.w_gate_up = p;
     hipLaunchKernelGGL(pack_rows_kernel, dim3(2 * f.mlp_inter), dim3(256), 0, st, (const bf16*)src->w_gate_up,
-                       (const bf16*)src->ln2_g, reinterpret_cast<bf16*>(p), f.hidden, f.mlp_inter);
+                       (const bf16*)src->ln2_g, reinterpret_cast<bf16*>(p), f.hidden, (int)PACK_GATE_UP, f.mlp_inter, 0);
     RS_HIP(hipGetLastError());
     p += align_up(2 * I * H * 2, 256);
     RS_HIP(copy(src->w_down, H * I * 2, &o.w_down));

@@ -42,7 +42,7 @@ def tiny_cfg(**kw):
 
 @pytest.mark.parametrize("bad", [
     dict(hidden=200), dict(head_dim=96), dict(n_kv_heads=3), dict(mlp_inter=1000), dict(max_tokens_per_call=0),
-    dict(hidden=0), dict(rope_theta=-1.0), dict(max_pos=0), dict(n_q_heads=3, n_kv_heads=1),
+    dict(hidden=0), dict(rope_theta=-1.0), dict(max_pos=0), dict(hidden=288), dict(mlp_inter=1056),
 ])
 def test_ctx_create_rejects_unsupported_shapes(lib, bad):
     with pytest.raises(RsError) as e:

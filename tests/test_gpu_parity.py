@@ -154,6 +154,18 @@ def test_tiny_two_layers_and_head_dim_128():
         cur = y_ref
 
 
+def test_odd_head_counts_and_widths():
+    """3 query heads on 1 KV head, widths that are not multiples of 256: 10 / 10 / 28 output units in the GEMMs."""
+    shape = synth.LayerShape("odd", 320, 3, 1, 64, 448)
+    w = synth.layer_weights(shape, 91, qkv_bias=True, gains="uniform")
+    x = synth.prompt_rows([("image", 140), ("text", 131)], shape.hidden, 92)
+    y_ref, k_ref, v_ref = layer_forward(x, LayerParams.from_arrays(shape, w))
+    (y, k, v), = run_single_request(shape, [w], x, [(0, 257), (257, 271)], qkv_bias=True, max_tokens=257)
+    check("odd Y", y, y_ref)
+    check("odd K", k, k_ref)
+    check("odd V", v, v_ref)
+
+
 # ------------------------------------------------------------------ micro-batches (Algorithm 2's S)
 def run_batch(shape, w, reqs, *, capacity, order=None):
     R = _runner()
