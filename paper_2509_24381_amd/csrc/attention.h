@@ -215,11 +215,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
         __syncthreads();
     }
 
-    // ---- normalise and store.  acc_o[t][r]: d = t*32 + 8*(r>>2) + 4*half + (r&3), query = this lane's row
+    // ---- normalise and store.  acc_o[t][r]: d = t*32 + 8*(r>>2) + 4*half + (r&3), query = this lane's row.
+    //      The output is the output projection's token operand: fragment-major of width ld_out (blocks of 32 tokens x 16
+    //      features, the two 8-feature halves 512 bytes apart, tokens 16 bytes apart).
     const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
     if (row < rows_total) {
         const float inv = 1.0f / l_tot;
-        bf16* op = out + (size_t)(rq.row0 + tok) * ld_out + head * D + 4 * half;
+        const uint32_t m = (uint32_t)(rq.row0 + tok);
+        char* op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u + half * 8;
+        const int ks0 = (head * D) >> 4;
 #pragma unroll
         for (int t = 0; t < DT; ++t)
 #pragma unroll
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc_o[t][4 * q + e] * inv);
-                *reinterpret_cast<bf16x4*>(op + t * 32 + 8 * q) = o;
+                *reinterpret_cast<bf16x4*>(op + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o;
             }
     }
 }

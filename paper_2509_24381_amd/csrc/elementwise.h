@@ -24,6 +24,34 @@ __global__ __launch_bounds__(256) void row_inv_rms_kernel(const bf16* __restrict
     if (lane == 0) inv_rms[row] = rsqrtf(ss / (float)H + eps);
 }
 
+// ---------------------------------------------------------------- row-major -> fragment-major copy of the layer input
+// dst holds x in the GEMMs' token-operand layout: blocks of 32 tokens x 16 features, the two 8-feature halves 512 bytes
+// apart, tokens 16 bytes apart (rows of the last block past `rows` are left untouched: they are never used).  One
+// workgroup moves 32 tokens x 128 features: 8 threads read one token's 256 contiguous bytes, and the 8 tokens of a
+// wavefront's 16-byte chunks of one (k-step, half) land in 128 contiguous bytes.
+__global__ __launch_bounds__(256) void to_fragment_major_kernel(const bf16* __restrict__ x, bf16* __restrict__ dst, int rows, int H) {
+    const int mb = blockIdx.x;
+    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
+    const int m = mb * 32 + r;
+    if (m >= rows) return;
+    const char* src = reinterpret_cast<const char*>(x + (size_t)m * H) + c * 16;
+    char* out = reinterpret_cast<char*>(dst) + ((size_t)mb * (H >> 4) * 2 + c) * 512 + r * 16;
+    for (int k0 = blockIdx.y * 64; k0 < H; k0 += gridDim.y * 64)  // 64 features = 8 chunks = 4 k-steps x 2 halves
+        st_global_16(out + (size_t)(k0 >> 4) * 1024, ld_global_16(src + (size_t)k0 * 2));
+}
+
+// inv_rms[m] = rsqrt(sum_u rowss[m][u] / H + eps): closes the per-row sums of squares left by the EPI_RESIDUAL epilogue.
+__global__ __launch_bounds__(256) void rowss_finalize_kernel(const float* __restrict__ rowss, int units, int M, int H,
+                                                             float eps, float* __restrict__ inv_rms) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    float ss = 0.0f;
+    for (int u = lane; u < units; u += WAVE) ss += rowss[(size_t)m * units + u];
+    ss = wave_sum(ss);
+    if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)H + eps);
+}
+
 // ---------------------------------------------------------------- K / V append
 struct KVBlockItem {
     int req;

@@ -39,30 +39,35 @@ enum GemmEpilogue {
 };
 
 struct GemmArgs {
-    const bf16* X;      // [M, K] activations, row stride ldx elements
+    const bf16* X;      // [M, K] activations, fragment-major (frag_offset_bytes with width K), blocks of 32 tokens
     const bf16* W;      // [N, K] packed weights, row stride K
-    bf16* out;          // [M, ldo]
+    bf16* out;          // [M, ldo], row-major or (out_frag) fragment-major of width ldo
     const bf16* bias;   // [N] in the original feature order, or null
-    const bf16* resid;  // [M, ldr]
+    const bf16* resid;  // [M, ldr], row-major or (resid_frag) fragment-major of width ldr
+    float* rowss;       // EPI_RESIDUAL: [M][N/32] sum of squares of each stored run of 32 features, or null
     float* partial;     // [splits, M, N]
     const float* row_scale;  // [M] 1/rms of the row (EPI_QKV_ROPE, EPI_SWIGLU)
     const int* row_pos;      // [M] absolute position of the row (EPI_QKV_ROPE)
     const float2* rope_cs;   // [max_pos][head_dim/2] (cos, sin)
     int rope_cols;           // columns [0, rope_cols) are q and k heads (a multiple of head_dim)
     int head_dim;            // 64 or 128
-    int ldx, ldo, ldr;
+    int ldo, ldr;
+    int out_frag, resid_frag;
     int M, N, K;
     int tiles_m;             // ceil(M / 256)
     int strips;              // strips per 256-row block; grid.x = tiles_m * strips
-    int stages_per_split;    // K/32 stages handled by one blockIdx.y
+    int steps_per_split;     // K/64 steps handled by one blockIdx.y
+#ifdef RS_GEMM_TIMING
+    unsigned long long* dbg;  // development only: [grid.x][2] shader-clock stamps at workgroup start and end
+#endif
 };
 
 constexpr int GS_BM = 256;
-constexpr int GS_BK = 32, GS_STAGES = 4;
-constexpr int GS_X_BYTES = GS_BM * GS_BK * 2;        // 16 KB: the token rows of one stage
-constexpr int GS_STAGE_BYTES = 2 * GS_X_BYTES;       // + up to 256 weight rows
-constexpr int GS_LDS_BYTES = GS_STAGES * GS_STAGE_BYTES;
+constexpr int GS_BK = 64;                            // K per pipeline step
 constexpr int GS_MAX_NT = 8;                         // units per tile
+constexpr int GS_SLOT_BYTES = GS_MAX_NT * 32 * GS_BK * 2;  // 32 KB: up to 256 weight rows of one step
+constexpr int GS_SLOTS = 4;
+constexpr int GS_LDS_BYTES = GS_SLOTS * GS_SLOT_BYTES;
 
 // silu(g) = g / (1 + 2^(-g log2 e)) with the raw v_exp_f32 / v_rcp_f32 instructions (1 ulp each; the result is rounded to bf16)
 RS_DEVICE float silu_f32(float g) {
@@ -77,6 +82,14 @@ RS_DEVICE void static_for(F&& f) {
     }
 }
 
+// Fragment-major activation layout: a [M, W] bf16 matrix is cut into blocks of 32 tokens x 16 features; inside a block the
+// two 8-feature halves are 512 bytes apart and the 32 tokens 16 bytes apart, so that the 64 lanes of a wavefront, each
+// holding 8 consecutive features of one token (the MFMA operand layout), read or write one contiguous kilobyte.
+// Byte offset of element (m, n); n's low 3 bits select the element inside the 16-byte chunk.
+RS_DEVICE uint32_t frag_offset_bytes(uint32_t m, uint32_t n, uint32_t width) {
+    return ((((m >> 5) * (width >> 4) + (n >> 4)) * 2u + ((n >> 3) & 1u)) * 32u + (m & 31u)) * 16u + (n & 7u) * 2u;
+}
+
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -87,14 +100,17 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 template <int EPI, int NT>
 RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base, int unit0, int half, int l32, int split) {
     constexpr int RSRC_FLAGS = 0x00020000;
+    const int m_pad = (a.M + 31) & ~31;  // fragment-major buffers hold whole blocks of 32 tokens
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int m = m_base + j * 32 + l32;
         if constexpr (EPI == EPI_SWIGLU) {
-            const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
+            // the output is the next GEMM's token operand: always fragment-major.  Unit u holds features 16u..16u+15 = one
+            // k-step of it, q selects the 8-feature half, so the 64 lanes of a store cover 512 contiguous bytes
+            const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, m_pad * a.ldo * 2, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t r_sc = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_scale, 0, a.M * 4, RSRC_FLAGS);
             const float sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r_sc, m * 4, 0, 0));
-            const uint32_t orow = ((uint32_t)m * (uint32_t)a.ldo + 4u * half) * 2u;
+            const uint32_t oblk = (uint32_t)(m >> 5) * (uint32_t)(a.ldo >> 4) * 1024u + (uint32_t)l32 * 16u + (uint32_t)half * 8u;
 #pragma unroll
             for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -104,7 +120,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     for (int e = 0; e < 4; ++e)
                         o[e] = f32_to_bf16(silu_f32(acc[i][j][4 * q + e] * sc) * (acc[i][j][8 + 4 * q + e] * sc));
                     __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out,
-                                                          orow + (uint32_t)((unit0 + i) * 16 + 8 * q) * 2u, 0, 0);
+                                                          oblk + (uint32_t)((unit0 + i) * 2 + q) * 512u, 0, 0);
                 }
         } else if constexpr (EPI == EPI_QKV_ROPE) {
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
@@ -178,21 +194,37 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), r_out, orow + (uint32_t)n * 4u, 0, 0);
                 }
         } else {
-            const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
-            const __amdgpu_buffer_rsrc_t r_res = __builtin_amdgcn_make_buffer_rsrc((void*)a.resid, 0, a.M * a.ldr * 2, RSRC_FLAGS);
+            // residual input and output are row-major [M, ld] or fragment-major (blocks of 32 tokens, padded to whole blocks)
+            const __amdgpu_buffer_rsrc_t r_out =
+                __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, (a.out_frag ? m_pad : a.M) * a.ldo * 2, RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t r_res =
+                __builtin_amdgcn_make_buffer_rsrc((void*)a.resid, 0, (a.resid_frag ? m_pad : a.M) * a.ldr * 2, RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t r_ss =
+                __builtin_amdgcn_make_buffer_rsrc((void*)a.rowss, 0, a.rowss != nullptr ? a.M * (a.N >> 5) * 4 : 0, RSRC_FLAGS);
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+            for (int i = 0; i < NT; ++i) {
+                float ss = 0.0f;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = (unit0 + i) * 32 + 8 * q + 4 * half;
-                    const bf16x4 r4 = __builtin_bit_cast(
-                        bf16x4, __builtin_amdgcn_raw_buffer_load_b64(r_res, ((uint32_t)m * (uint32_t)a.ldr + (uint32_t)n) * 2u, 0, 0));
+                    const uint32_t n = (uint32_t)((unit0 + i) * 32 + 8 * q + 4 * half);
+                    const uint32_t roff = a.resid_frag ? frag_offset_bytes(m, n, a.ldr) : ((uint32_t)m * (uint32_t)a.ldr + n) * 2u;
+                    const uint32_t ooff = a.out_frag ? frag_offset_bytes(m, n, a.ldo) : ((uint32_t)m * (uint32_t)a.ldo + n) * 2u;
+                    const bf16x4 r4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_raw_buffer_load_b64(r_res, roff, 0, 0));
                     bf16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc[i][j][4 * q + e] + bf16_to_f32(r4[e]));
-                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out,
-                                                          ((uint32_t)m * (uint32_t)a.ldo + (uint32_t)n) * 2u, 0, 0);
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] = f32_to_bf16(acc[i][j][4 * q + e] + bf16_to_f32(r4[e]));
+                        const float st = bf16_to_f32(o[e]);
+                        ss += st * st;
+                    }
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out, ooff, 0, 0);
                 }
+                // the two half-waves hold the two halves of this token's 32 features of the unit; half 0 stores the sum
+                // (an empty resource when no sums are wanted; half 1 and rows past M aim outside it)
+                ss += __shfl_xor(ss, 32, WAVE);
+                const uint32_t soff = half ? 0x80000000u : ((uint32_t)m * (uint32_t)(a.N >> 5) + (uint32_t)(unit0 + i)) * 4u;
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss), r_ss, soff, 0, 0);
+            }
         }
     }
 }
@@ -200,32 +232,14 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
 #define RS_DS_READ_B128(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
 #define RS_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// "s_waitcnt lgkmcnt(0)" tied by register operands to the fragments it guards, so the MFMAs that consume them stay below it
+// "s_waitcnt lgkmcnt(0)" tied by register operands to the weight fragments it guards, so the MFMAs that consume them
+// stay below it
 template <int NT>
-RS_DEVICE void tie_wait_lgkm0(bf16x8 (&w)[NT], bf16x8 (&x)[2]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]));
+RS_DEVICE void tie_wait_lgkm0(bf16x8 (&w)[NT]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w[0]));
 #pragma unroll
-    for (int i = 0; i < NT; ++i) asm volatile("" : "+v"(w[i]));
+    for (int i = 1; i < NT; ++i) asm volatile("" : "+v"(w[i]));
 }
-
-// waits until at most `stages` whole stages (4 + lw loads each) plus `extra` loads are still in flight
-RS_DEVICE void wait_loads_2stages(int lw) {
-    switch (lw) {
-        case 1: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
-        case 2: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-        case 3: asm volatile("s_waitcnt vmcnt(14)" ::: "memory"); break;
-        default: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-    }
-}
-RS_DEVICE void wait_loads_1stage_plus_x(int lw) {
-    switch (lw) {
-        case 1: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
-        case 2: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
-        case 3: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
-        default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-    }
-}
-
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -236,6 +250,10 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     const int half = lane >> 5;
     const int l32 = lane & 31;
 
+#ifdef RS_GEMM_TIMING
+    unsigned long long dbg_t0;
+    asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_t0));
+#endif
     // ---- which strip: workgroup ids are dispatched round-robin over the 8 XCDs; re-map them so that each XCD owns a
     //      contiguous range of strips (all token blocks of a weight range run on one XCD, close in time: the weight stream
     //      crosses the L2 boundary once)
@@ -248,58 +266,75 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     const int strip = logical / a.tiles_m;
     const int m0 = tm * GS_BM;
 
-    // ---- the strip's units and its tiles (sizes differ by at most one, larger ones first)
+    // ---- the strip's units and its tiles (sizes differ by at most one, smaller ones first: the load stream then never
+    //      issues fewer loads per step than the waits of the tile being multiplied assume)
     const int nu = a.N >> 5;
     const int ub = nu / a.strips, ur = nu % a.strips;
     const int u_first = strip * ub + min(strip, ur);
     const int u_count = ub + (strip < ur ? 1 : 0);
     if (u_count == 0) return;  // more strips than units: never launched this way, and uniform for the whole workgroup
     const int ntiles = (u_count + GS_MAX_NT - 1) / GS_MAX_NT;
-    const int tb = u_count / ntiles, tr = u_count % ntiles;
-    const int lw = (tb + (tr > 0 ? 1 : 0) + 1) >> 1;  // W load instructions per wavefront per stage (64 rows each, workgroup-wide)
+    const int tb = u_count / ntiles;
+    const int n_small = ntiles - u_count % ntiles;  // tiles [0, n_small) have tb units, the rest tb + 1
 
     const int split = blockIdx.y;
-    const int stages_total = a.K / GS_BK;
-    const int st0 = split * a.stages_per_split;
-    const int ns = min(a.stages_per_split, stages_total - st0);  // stages per tile (>= 1)
-    const uint32_t k0 = (uint32_t)st0 * (GS_BK * 2);
+    const int steps_total = a.K / GS_BK;
+    const int st0 = split * a.steps_per_split;
+    const int ns = min(a.steps_per_split, steps_total - st0);  // K steps per tile (>= 1)
+    const uint32_t k0 = (uint32_t)st0 * (GS_BK * 2);         // byte offset of the K range in a weight row
+    const uint32_t xk0 = (uint32_t)st0 * 4096u;              // and in a fragment-major token block (4 k-steps of 1 KB)
 
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, a.M * a.ldx * 2, 0x00020000);
+    // ---- token fragments go global -> registers.  X is stored fragment-major (see frag_offset_bytes): the 16 bytes lane
+    //      (l32, half) feeds to k-step ks of token block mb sit at ((mb * K/16 + ks) * 2 + half) * 512 + l32 * 16, so one
+    //      load instruction of a wavefront fetches one contiguous kilobyte (8 whole cache lines).  Token blocks past M
+    //      fall outside the buffer resource and read as zeros.  These are ordinary loads the compiler can see: it places
+    //      the vmcnt wait in front of their first use itself (a hand-placed wait on inline-asm loads would not stop the
+    //      register allocator from copying a register whose load is still in flight).
+    const uint32_t x_block_bytes = (uint32_t)(a.K >> 4) * 1024u;  // one block of 32 tokens, all of K
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, ((a.M + 31) >> 5) * (int)x_block_bytes, 0x00020000);
+    const uint32_t xv0 = (uint32_t)((m0 >> 5) + wave * 2) * x_block_bytes + (uint32_t)half * 512u + (uint32_t)l32 * 16u;
+    const uint32_t xv1 = xv0 + x_block_bytes;
+    uint32_t x_koff = xk0;  // byte offset of the next step to load inside a token block
+    int x_s = 0;
+    bf16x8 xA[2][4], xB[2][4];
+    auto load_x = [&](auto oc, bf16x8 (&xn)[2][4]) {  // load number o of a step: (j, kk) = (o >> 2, o & 3)
+        constexpr int o = decltype(oc)::value;
+        const uint32_t voff = ((o >> 2) ? xv1 : xv0) + (uint32_t)((o & 3) * 1024);
+        xn[o >> 2][o & 3] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rx, voff, x_koff, 0));
+    };
+    auto x_advance = [&]() {  // the same rows are walked again for every tile; past the last tile the loads are idle repeats
+        x_koff += 4096;
+        if (++x_s == ns) {
+            x_s = 0;
+            x_koff = xk0;
+        }
+    };
+
+    // ---- weight rows go global -> LDS by DMA: load instruction k of this wavefront fills rows [(wave + 4k)*8, +8) of the
+    //      step's slot, each lane fetching the 16-byte chunk that belongs in its (swizzled) place
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.W, 0, a.N * a.K * 2, 0x00020000);
-
-    // ---- loader geometry: load instruction i of this wavefront fills LDS rows [i*64 + wave*16, +16) of the operand's stage,
-    //      each lane fetching the 16-byte chunk that belongs in its slot
-    const int ld_r = wave * 16 + (lane >> 2);
-    const uint32_t ld_c = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3));
-    const uint32_t vx0 = (uint32_t)(m0 + ld_r) * (uint32_t)a.ldx * 2u + ld_c * 16u;  // instruction i: + i * x_step
-    const uint32_t vw0 = (uint32_t)ld_r * (uint32_t)a.K * 2u + ld_c * 16u;             // instruction k: + k * w_step
-    const uint32_t x_step = 64u * (uint32_t)a.ldx * 2u, w_step = 64u * (uint32_t)a.K * 2u;
-    constexpr uint32_t DEAD = 0x80000000u;  // beyond any buffer this kernel is given: reads as zeros, moves no data
-
-    // ---- the load stream (runs ahead of the multiply, across tile boundaries)
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    int d_tile = 0, d_s = 0;
-    uint32_t d_slot = 0;              // byte offset of the ring slot being filled
-    uint32_t d_koff = k0;             // byte offset of the stage's k range inside a row
-    uint32_t d_wsoff = 0;             // byte offset of the tile's first weight row
-    uint32_t d_vx = vx0;              // this wavefront's X row offset (DEAD once the stream is past the last tile)
-    uint32_t d_vw0, d_vw1, d_vw2, d_vw3;  // W row offset per load instruction (DEAD: no such row in the tile)
+    const uint32_t ld_c = (uint32_t)((lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7));
+    const uint32_t vw0 = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)a.K * 2u + ld_c * 16u;
+    const uint32_t w_step = 32u * (uint32_t)a.K * 2u;  // instruction k + 1 is 32 rows further
+    constexpr uint32_t DEAD = 0x80000000u;  // beyond any buffer this kernel is given: reads as zeros, moves no data
+    int d_tile = 0, d_s = 0, d_nt = 0;
+    uint32_t d_slot = 0;    // byte offset of the ring slot being filled
+    uint32_t d_koff = k0;
+    uint32_t d_wsoff = 0;   // byte offset of the tile's first weight row
+    uint32_t d_vw = DEAD;
     // (written without branches: stores to different variables in the two arms of an "if" get merged by the compiler into
     // one store through a selected address, which keeps that state in scratch memory)
     auto stream_enter_tile = [&]() {
         const bool in_strip = d_tile < ntiles;  // past the strip's last tile the remaining loads of the pipeline move nothing
-        const int nt = tb + (d_tile < tr ? 1 : 0);
-        const int unit0 = u_first + d_tile * tb + min(d_tile, tr);
-        const int live = in_strip ? nt * 32 - wave * 16 : 0;  // load instruction k covers rows k*64 + wave*16 .. of the tile
+        const int unit0 = u_first + d_tile * tb + max(d_tile - n_small, 0);
+        d_nt = tb + (d_tile >= n_small ? 1 : 0);
         d_wsoff = in_strip ? (uint32_t)unit0 * 32u * (uint32_t)a.K * 2u : 0u;
-        d_vx = in_strip ? vx0 : DEAD;
-        d_vw0 = (0 < live) ? vw0 : DEAD;
-        d_vw1 = (64 < live) ? vw0 + w_step : DEAD;
-        d_vw2 = (128 < live) ? vw0 + 2 * w_step : DEAD;
-        d_vw3 = (192 < live) ? vw0 + 3 * w_step : DEAD;
+        d_vw = in_strip ? vw0 : DEAD;
     };
     auto stream_advance = [&]() {
-        d_slot = (d_slot + GS_STAGE_BYTES) & (GS_LDS_BYTES - 1);
+        d_slot = (d_slot + GS_SLOT_BYTES) & (GS_LDS_BYTES - 1);
         d_koff += GS_BK * 2;
         if (++d_s == ns) {
             d_s = 0;
@@ -308,47 +343,38 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
             stream_enter_tile();
         }
     };
-    // The row part of an address goes into the vector offset, which is what the buffer range check looks at (the scalar
-    // offset is excluded from it): rows past M must stay visible to the check.  DEAD + i * x_step stays out of range.
-    auto stream_load_x = [&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + d_slot + wave * 1024 + i * 4096);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(uintptr_t)dst, 16, d_vx + i * x_step,
-                                                 __builtin_amdgcn_readfirstlane(d_koff), 0, 0);
-    };
-    auto stream_load_w = [&](auto kc) {
+    auto load_w = [&](auto kc) {
         constexpr int k = decltype(kc)::value;
-        if (k < lw) {
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + d_slot + GS_X_BYTES + wave * 1024 + k * 4096);
-            const uint32_t voff = (k == 0) ? d_vw0 : (k == 1) ? d_vw1 : (k == 2) ? d_vw2 : d_vw3;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(uintptr_t)dst, 16, voff,
-                                                     __builtin_amdgcn_readfirstlane(d_wsoff + d_koff), 0, 0);
-        }
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + d_slot + wave * 1024 + k * 4096);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr)(uintptr_t)dst, 16, d_vw + k * w_step,
+                                                 __builtin_amdgcn_readfirstlane(d_wsoff + d_koff), 0, 0);
     };
 
-    // ---- fragment addresses (bytes from the start of a stage); kk selects the 16-wide k-step inside the stage
-    const uint32_t sw = (uint32_t)((l32 >> 2) & 3);
-    uint32_t ax[2], aw[2];
+    // ---- weight fragment addresses inside a slot: row l32 of unit i at i*4096 + l32*128, chunk (2 kk + half) swizzled
+    uint32_t aw[4];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        const uint32_t slot = ((uint32_t)(kk * 2 + half) ^ sw) * 16u;
-        ax[kk] = lds0 + (uint32_t)(wave * 64 + l32) * 64u + slot;
-        aw[kk] = lds0 + (uint32_t)GS_X_BYTES + (uint32_t)l32 * 64u + slot;
-    }
-    uint32_t c_slot = 0;  // ring slot of the stage being multiplied
+    for (int kk = 0; kk < 4; ++kk)
+        aw[kk] = lds0 + (uint32_t)l32 * 128u + (((uint32_t)(kk * 2 + half) ^ (uint32_t)((l32 >> 1) & 7)) * 16u);
+    uint32_t c_slot = 0;  // ring slot of the step being multiplied
 
-    // ---- fill the pipeline: three stages
+    // ---- fill the pipeline: W(0), W(1), X(0), W(2)
     stream_enter_tile();
-    static_for<0, 3>([&](auto) {
-        static_for<0, 4>([&](auto ic) { stream_load_x(ic); });
-        static_for<0, 4>([&](auto kc) { stream_load_w(kc); });
+    auto prologue_w = [&]() {
+        static_for<0, GS_MAX_NT>([&](auto kc) {
+            if (decltype(kc)::value < d_nt) load_w(kc);
+        });
         stream_advance();
-    });
+    };
+    prologue_w();
+    prologue_w();
+    static_for<0, 8>([&](auto oc) { load_x(oc, xA); });
+    x_advance();
+    prologue_w();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     auto run_tile = [&](auto ntc, const int unit0) {
         constexpr int NT = decltype(ntc)::value;
-        constexpr int SL = 2 * NT;   // MFMAs (= slots for memory instructions) per half stage
-        constexpr int LA = NT + 6;   // memory instructions per half stage: NT + 2 fragment reads, 4 loads
+        constexpr int SL = 2 * NT;   // MFMAs (= slots for memory instructions) per k-step
         f32x16 acc[NT][2];
 #pragma unroll
         for (int i = 0; i < NT; ++i)
@@ -356,69 +382,83 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        bf16x8 w0[NT], x0[2], w1[NT], x1[2];
+        bf16x8 wa[NT], wb[NT];
 
-        // fragment read number o of a half stage: x[0], w[0], x[1], w[1], w[2], ...
-        auto read_frag = [&](auto oc, bf16x8 (&wf)[NT], bf16x8 (&xf)[2], const uint32_t awv, const uint32_t axv) {
-            constexpr int o = decltype(oc)::value;
-            if constexpr (o == 0) RS_DS_READ_B128(xf[0], axv, 0);
-            else if constexpr (o == 2) RS_DS_READ_B128(xf[1], axv, 2048);
-            else if constexpr (o == 1) RS_DS_READ_B128(wf[0], awv, 0);
-            else RS_DS_READ_B128(wf[o - 2], awv, (o - 2) * 2048);
+        auto read_w = [&](auto ic, bf16x8 (&wf)[NT], const uint32_t addr) {
+            constexpr int i = decltype(ic)::value;
+            RS_DS_READ_B128(wf[i], addr, i * 4096);
         };
-
-        // the tile's first stage has landed (its loads were issued at least two stages of work ago)
-        wait_loads_2stages(lw);
-        asm volatile("s_barrier" ::: "memory");
-        static_for<0, NT + 2>([&](auto oc) { read_frag(oc, w0, x0, aw[0] + c_slot, ax[0] + c_slot); });
-
-        for (int s = 0; s < ns; ++s) {
-            const uint32_t n_slot = (c_slot + GS_STAGE_BYTES) & (GS_LDS_BYTES - 1);
-            const uint32_t aw1 = aw[1] + c_slot, ax1 = ax[1] + c_slot;
-            const uint32_t aw0 = aw[0] + n_slot, ax0 = ax[0] + n_slot;
-            tie_wait_lgkm0<NT>(w0, x0);
-            // ---- first half: MFMAs on the kk=0 fragments; behind them the kk=1 fragment reads, then the X loads of stage s+3
+        // one k-step of 2 NT MFMAs on (wf, xc[.][KK]); memory instruction number o of the phase rides behind MFMA number
+        // o (or several per MFMA when there are more instructions than MFMAs): first the NT fragment reads of the next
+        // k-step, then the phase's EXTRA loads
+        auto phase = [&](auto kkc, bf16x8 (&wf)[NT], bf16x8 (&xc)[2][4], bf16x8 (&wnext)[NT], const uint32_t wnext_addr,
+                         auto extra_count, auto&& extra) {
+            constexpr int KK = decltype(kkc)::value;
+            constexpr int LA = NT + decltype(extra_count)::value;
             static_for<0, SL>([&](auto qc) {
                 constexpr int q = decltype(qc)::value;
                 constexpr int i = q >> 1, j = q & 1;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[i], x0[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xc[j][KK], acc[i][j], 0, 0, 0);
                 constexpr int o_lo = (LA <= SL) ? (q < LA ? q : LA) : (q * LA / SL);
                 constexpr int o_hi = (LA <= SL) ? (q + 1 < LA ? q + 1 : LA) : ((q + 1) * LA / SL);
                 static_for<o_lo, o_hi>([&](auto oc) {
                     constexpr int o = decltype(oc)::value;
-                    if constexpr (o < NT + 2) read_frag(oc, w1, x1, aw1, ax1);
-                    else stream_load_x(std::integral_constant<int, o - (NT + 2)>{});
+                    if constexpr (o < NT) read_w(oc, wnext, wnext_addr);
+                    else extra(std::integral_constant<int, o - NT>{});
                 });
                 RS_FENCE();
             });
-            tie_wait_lgkm0<NT>(w1, x1);  // also: every LDS read of this stage has landed before the barrier frees its slot
-            wait_loads_1stage_plus_x(lw);
+        };
+        // one step of K = 64: the token fragments of the next step are loaded into xn behind k-steps 0 and 1; the
+        // barrier in the middle publishes the weights of the next step, whose first fragments are read behind k-step 3
+        // together with the DMA of the weights three steps ahead
+        auto step = [&](bf16x8 (&xc)[2][4], bf16x8 (&xn)[2][4]) {
+            const uint32_t n_slot = (c_slot + GS_SLOT_BYTES) & (GS_LDS_BYTES - 1);
+            tie_wait_lgkm0<NT>(wa);
+            phase(std::integral_constant<int, 0>{}, wa, xc, wb, aw[1] + c_slot, std::integral_constant<int, 4>{},
+                  [&](auto ec) { load_x(ec, xn); });
+            tie_wait_lgkm0<NT>(wb);
+            phase(std::integral_constant<int, 1>{}, wb, xc, wa, aw[2] + c_slot, std::integral_constant<int, 4>{},
+                  [&](auto ec) { load_x(std::integral_constant<int, decltype(ec)::value + 4>{}, xn); });
+            x_advance();
+            tie_wait_lgkm0<NT>(wa);  // also: every LDS read of k-steps 0..2 has landed
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(16 + NT) : "memory");  // this wavefront's share of the next W step
             asm volatile("s_barrier" ::: "memory");
             RS_FENCE();
-            // ---- second half: MFMAs on the kk=1 fragments; behind them the next stage's kk=0 fragment reads, then the W loads
-            static_for<0, SL>([&](auto qc) {
-                constexpr int q = decltype(qc)::value;
-                constexpr int i = q >> 1, j = q & 1;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1[i], x1[j], acc[i][j], 0, 0, 0);
-                constexpr int o_lo = (LA <= SL) ? (q < LA ? q : LA) : (q * LA / SL);
-                constexpr int o_hi = (LA <= SL) ? (q + 1 < LA ? q + 1 : LA) : ((q + 1) * LA / SL);
-                static_for<o_lo, o_hi>([&](auto oc) {
-                    constexpr int o = decltype(oc)::value;
-                    if constexpr (o < NT + 2) read_frag(oc, w0, x0, aw0, ax0);
-                    else stream_load_w(std::integral_constant<int, o - (NT + 2)>{});
-                });
-                RS_FENCE();
-            });
+            constexpr int W_A = (NT + 1) / 2, W_B = NT - W_A;
+            phase(std::integral_constant<int, 2>{}, wa, xc, wb, aw[3] + c_slot, std::integral_constant<int, W_A>{},
+                  [&](auto ec) { load_w(ec); });
+            tie_wait_lgkm0<NT>(wb);
+            phase(std::integral_constant<int, 3>{}, wb, xc, wa, aw[0] + n_slot, std::integral_constant<int, W_B>{},
+                  [&](auto ec) { load_w(std::integral_constant<int, decltype(ec)::value + W_A>{}); });
+            if (d_nt > NT) load_w(std::integral_constant<int, NT < GS_MAX_NT ? NT : 0>{});  // the stream is in a wider tile
             stream_advance();
             c_slot = n_slot;
+        };
+
+        // tile start: xA holds (or is receiving) the tile's first token fragments; its first weight step was published by
+        // the previous tile's last barrier (by the prologue for the first tile)
+        asm volatile("s_barrier" ::: "memory");
+        static_for<0, NT>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
+        int s = 0;
+        for (; s + 1 < ns; s += 2) {
+            step(xA, xB);
+            step(xB, xA);
         }
-        tie_wait_lgkm0<NT>(w0, x0);  // the look-ahead read behind the last stage (discarded: the next tile reads its own)
+        if (s < ns) {  // odd number of steps: one more, then move the fragments in flight back to xA
+            step(xA, xB);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) xA[j][kk] = xB[j][kk];
+        }
+        tie_wait_lgkm0<NT>(wa);  // the look-ahead read behind the last step (discarded: the next tile reads its own)
         gemm_epilogue<EPI, NT>(a, acc, m0 + wave * 64, unit0, half, l32, split);
     };
 
     for (int t = 0; t < ntiles; ++t) {
-        const int nt = tb + (t < tr ? 1 : 0);
-        const int unit0 = u_first + t * tb + min(t, tr);
+        const int nt = tb + (t >= n_small ? 1 : 0);
+        const int unit0 = u_first + t * tb + max(t - n_small, 0);
         switch (nt) {
             case 1: run_tile(std::integral_constant<int, 1>{}, unit0); break;
             case 2: run_tile(std::integral_constant<int, 2>{}, unit0); break;
@@ -431,20 +471,31 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stream's last (empty) loads still target this workgroup's LDS
+#ifdef RS_GEMM_TIMING
+    if (tid == 0 && blockIdx.y == 0) {
+        unsigned long long dbg_t1;
+        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_t1));
+        a.dbg[blockIdx.x * 2] = dbg_t0;
+        a.dbg[blockIdx.x * 2 + 1] = dbg_t1;
+    }
+#endif
 }
 
 // Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).
-// One wavefront per row; when inv_rms is given it also leaves rsqrt(mean(out[m,:]^2) + eps) of the stored row there.
+// One wavefront per row; resid / out are row-major or fragment-major (see frag_offset_bytes); when inv_rms is given it
+// also leaves rsqrt(mean(out[m,:]^2) + eps) of the stored row there.
 __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float* __restrict__ partial, int splits,
-                                                                     const bf16* __restrict__ resid, int ldr,
-                                                                     bf16* __restrict__ out, int ldo, int M, int N,
+                                                                     const bf16* __restrict__ resid, int ldr, int resid_frag,
+                                                                     bf16* __restrict__ out, int ldo, int out_frag, int M, int N,
                                                                      float* __restrict__ inv_rms, float eps) {
     const int lane = threadIdx.x & 63;
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     float ss = 0.0f;
     for (int n = lane * 4; n < N; n += WAVE * 4) {
-        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(resid + (size_t)m * ldr + n);
+        const size_t roff = resid_frag ? frag_offset_bytes(m, n, ldr) : ((size_t)m * ldr + n) * 2;
+        const size_t ooff = out_frag ? frag_offset_bytes(m, n, ldo) : ((size_t)m * ldo + n) * 2;
+        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const char*>(resid) + roff);
         float v[4] = {bf16_to_f32(r4[0]), bf16_to_f32(r4[1]), bf16_to_f32(r4[2]), bf16_to_f32(r4[3])};
         for (int s = 0; s < splits; ++s) {
             f32x4 p = *reinterpret_cast<const f32x4*>(partial + ((size_t)s * M + m) * N + n);
@@ -456,7 +507,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float
             const float st = bf16_to_f32(o[e]);
             ss += st * st;
         }
-        *reinterpret_cast<bf16x4*>(out + (size_t)m * ldo + n) = o;
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<char*>(out) + ooff) = o;
     }
     if (inv_rms != nullptr) {
         ss = wave_sum(ss);

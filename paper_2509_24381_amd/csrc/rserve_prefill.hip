@@ -109,7 +109,7 @@ int choose_splitk(const rs_ctx* c, int tiles_m, int units, int k_stages) {
 }
 
 struct WorkspaceLayout {
-    size_t qkv, attn, r, act, partial, inv_rms1, inv_rms2, desc, total;
+    size_t qkv, xf, attn, r, act, partial, inv_rms1, inv_rms2, rowss, desc, total;
 };
 
 WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
@@ -122,13 +122,16 @@ WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
         return o;
     };
     const size_t t = (size_t)std::max(T, 1);
+    const size_t tp = align_up(t, 32);  // fragment-major buffers hold whole blocks of 32 tokens
     w.qkv = take(t * c->qkv_dim * 2);
-    w.attn = take(t * c->q_dim * 2);
-    w.r = take(t * f.hidden * 2);
-    w.act = take(t * f.mlp_inter * 2);
+    w.xf = take(tp * f.hidden * 2);
+    w.attn = take(tp * c->q_dim * 2);
+    w.r = take(tp * f.hidden * 2);
+    w.act = take(tp * f.mlp_inter * 2);
     w.partial = take(4 * t * f.hidden * 4);  // up to 4 split-K partial planes of [T, H] fp32
-    w.inv_rms1 = take(t * 4);
-    w.inv_rms2 = take(t * 4);
+    w.inv_rms1 = take(tp * 4);
+    w.inv_rms2 = take(tp * 4);
+    w.rowss = take(tp * (f.hidden / 32) * 4);
     w.desc = take(desc_sizes(c, T, R).total);
     w.total = off;
     return w;
@@ -138,21 +141,23 @@ template <int EPI>
 rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     a.tiles_m = (a.M + GS_BM - 1) / GS_BM;
     a.strips = strips_for(c, a.tiles_m, splits, a.N / 32);
-    const int stages = a.K / GS_BK;
-    a.stages_per_split = (stages + splits - 1) / splits;
-    splits = (stages + a.stages_per_split - 1) / a.stages_per_split;  // no empty K range
+    const int steps = a.K / GS_BK;
+    a.steps_per_split = (steps + splits - 1) / splits;
+    splits = (steps + a.steps_per_split - 1) / a.steps_per_split;  // no empty K range
     dim3 grid(a.tiles_m * a.strips, splits);
     hipLaunchKernelGGL(gemm_strip_kernel<EPI>, grid, dim3(256), GS_LDS_BYTES, st, a);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
 
-// out = resid + X W^T, through split-K partials when the unsplit launch would leave compute units idle.  When inv_rms_out
-// is given it receives rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input).
-rs_status gemm_residual(const rs_ctx* c, const bf16* X, int ldx, const bf16* W, const bf16* resid, bf16* out,
-                        int M, int N, int K, float* partial, float* inv_rms_out, hipStream_t st) {
+// out = resid + X W^T, through split-K partials when the unsplit launch would leave compute units idle.  X is fragment-
+// major; resid and out are row-major or fragment-major as flagged.  When inv_rms_out is given it receives
+// rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input); rowss is scratch for it.
+rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf16* resid, int resid_frag, bf16* out,
+                        int out_frag, int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, hipStream_t st) {
     GemmArgs a{};
-    a.X = X; a.ldx = ldx; a.W = W; a.out = out; a.ldo = N; a.resid = resid; a.ldr = N; a.partial = partial;
+    a.X = X; a.W = W; a.out = out; a.ldo = N; a.out_frag = out_frag; a.resid = resid; a.ldr = N; a.resid_frag = resid_frag;
+    a.partial = partial;
     a.M = M; a.N = N; a.K = K;
     const float eps = c->cfg.rms_eps;
     int splits = choose_splitk(c, (M + GS_BM - 1) / GS_BM, N / 32, K / GS_BK);
@@ -161,16 +166,18 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, int ldx, const bf16* W, 
         splits = (K / GS_BK + sps - 1) / sps;
     }
     if (splits == 1) {
+        a.rowss = inv_rms_out ? rowss : nullptr;
         rs_status s = launch_gemm<EPI_RESIDUAL>(c, a, 1, st);
         if (s != RS_OK || !inv_rms_out) return s;
-        hipLaunchKernelGGL(row_inv_rms_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const bf16*)out, inv_rms_out, M, N, eps);
+        hipLaunchKernelGGL(rowss_finalize_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)rowss, N / 32, M, N, eps,
+                           inv_rms_out);
         RS_HIP(hipGetLastError());
         return RS_OK;
     }
     rs_status s = launch_gemm<EPI_PARTIAL>(c, a, splits, st);
     if (s != RS_OK) return s;
     hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)partial, splits, resid, N,
-                       out, N, M, N, inv_rms_out, eps);
+                       resid_frag, out, N, out_frag, M, N, inv_rms_out, eps);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -309,12 +316,14 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     const int* d_rowpos = reinterpret_cast<const int*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks);
 
     bf16* qkv = reinterpret_cast<bf16*>(wsb + L.qkv);
+    bf16* xf = reinterpret_cast<bf16*>(wsb + L.xf);
     bf16* attn = reinterpret_cast<bf16*>(wsb + L.attn);
     bf16* r = reinterpret_cast<bf16*>(wsb + L.r);
     bf16* act = reinterpret_cast<bf16*>(wsb + L.act);
     float* partial = reinterpret_cast<float*>(wsb + L.partial);
     float* inv_rms1 = reinterpret_cast<float*>(wsb + L.inv_rms1);
     float* inv_rms2 = reinterpret_cast<float*>(wsb + L.inv_rms2);
+    float* rowss = reinterpret_cast<float*>(wsb + L.rowss);
     const bf16* xb = reinterpret_cast<const bf16*>(x);
     bf16* yb = reinterpret_cast<bf16*>(y);
     const int H = f.hidden, I = f.mlp_inter;
@@ -325,12 +334,15 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     tm.begin(RS_STEP_ROW_RMS);
     hipLaunchKernelGGL(row_inv_rms_kernel, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv_rms1, T, H, f.rms_eps);
     RS_HIP(hipGetLastError());
+    // and x in the GEMMs' fragment-major token-operand layout
+    hipLaunchKernelGGL(to_fragment_major_kernel, dim3((T + 31) / 32, std::min(8, H / 64)), dim3(256), 0, st, xb, xf, T, H);
+    RS_HIP(hipGetLastError());
     tm.end(RS_STEP_ROW_RMS);
     // qkv = rope( (x Wqkv'^T) / rms + b )
     tm.begin(RS_STEP_QKV_GEMM);
     {
         GemmArgs a{};
-        a.X = xb; a.ldx = H; a.W = (const bf16*)w->w_qkv; a.out = qkv; a.ldo = ctx->qkv_dim;
+        a.X = xf; a.W = (const bf16*)w->w_qkv; a.out = qkv; a.ldo = ctx->qkv_dim;
         a.bias = f.qkv_bias ? (const bf16*)w->b_qkv : nullptr;
         a.row_scale = inv_rms1; a.row_pos = d_rowpos; a.rope_cs = (const float2*)ctx->rope_dev;
         a.rope_cols = ctx->q_dim + ctx->kv_dim; a.head_dim = f.head_dim;
@@ -346,13 +358,13 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
-    if ((s = gemm_residual(ctx, attn, ctx->q_dim, (const bf16*)w->w_o, xb, r, T, H, ctx->q_dim, partial, inv_rms2, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, attn, (const bf16*)w->w_o, xb, 0, r, 1, T, H, ctx->q_dim, partial, inv_rms2, rowss, st)) != RS_OK) return s;
     tm.end(RS_STEP_O_GEMM);
     // act = silu((r Wg'^T) / rms) * ((r Wu'^T) / rms)
     tm.begin(RS_STEP_GATE_UP_GEMM);
     {
         GemmArgs a{};
-        a.X = r; a.ldx = H; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I;
+        a.X = r; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I; a.out_frag = 1;
         a.row_scale = inv_rms2;
         a.M = T; a.N = 2 * I; a.K = H;
         if ((s = launch_gemm<EPI_SWIGLU>(ctx, a, 1, st)) != RS_OK) return s;
@@ -360,7 +372,7 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     tm.end(RS_STEP_GATE_UP_GEMM);
     // y = r + act Wd^T
     tm.begin(RS_STEP_DOWN_GEMM);
-    if ((s = gemm_residual(ctx, act, I, (const bf16*)w->w_down, r, yb, T, H, I, partial, nullptr, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, act, (const bf16*)w->w_down, r, 1, yb, 0, T, H, I, partial, nullptr, nullptr, st)) != RS_OK) return s;
     tm.end(RS_STEP_DOWN_GEMM);
 
     for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
