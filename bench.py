@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # Bytes crossing the L2 / fabric boundary per gate/up GEMM launch at T=2048 on the 7B shape, from the two rocprofv3 --pmc
 # passes summarised in profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
 # factors a plain copy kernel of known size gives).  Algorithmic bytes of the same launch: 363.9e6.
-GATE_UP_TRAFFIC_BYTES = (460235.0 * 2.0 + 75854.5 * 1.0) * 1024
+GATE_UP_TRAFFIC_BYTES = (459452.4 * 2.0 + 141568.0 * 1.0) * 1024
 
 
 def cpu_baseline(wl, w0, x, target_seconds: float):
@@ -137,7 +137,7 @@ def main():
                    "calls_per_step": calls_per_step, "shape": "hidden 3584, 28 q / 4 kv heads, head_dim 128, mlp 18944"},
         "tflops": tflops,
         "mfma_frac_whole_path": tflops / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
+        "roofline": {"kernel": "gemm_strip_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
                      "bound": "mfma", "achieved": gu_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": GATE_UP_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (L2/fabric boundary, rocprofv3 --pmc)", "algorithmic_bytes": 363.9e6,

@@ -100,12 +100,34 @@ int strips_for(const rs_ctx* c, int tiles_m, int splits, int units) {
     return std::max(1, std::min(units, c->n_cu / std::max(1, tiles_m * splits)));
 }
 
-int choose_splitk(const rs_ctx* c, int tiles_m, int units, int k_stages) {
-    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_stages));
-    // split K only while the unsplit launch cannot give every compute unit a strip
-    int s = 1;
-    while (s < 4 && tiles_m * std::min(units, c->n_cu / std::max(1, tiles_m)) * (s + 1) <= c->n_cu && k_stages / (s + 1) >= 16) ++s;
-    return s;
+// Estimated duration (shader clocks) of a residual GEMM cut into `splits` K ranges.  Constants fitted to measurements
+// on MI355X: a step of K = 64 costs 256 clocks of matrix-pipe issue per unit plus about 350 of barrier and issue overhead,
+// a tile about 20000 for pipeline fill and epilogue, and the reduction kernel moves its bytes at about 2 TB/s.
+double gemm_cost_clocks(const rs_ctx* c, int M, int units, int k_steps, int splits) {
+    const int tiles_m = (M + GS_BM - 1) / GS_BM;
+    const int strips = strips_for(c, tiles_m, splits, units);
+    const int waves = (tiles_m * strips * splits + c->n_cu - 1) / c->n_cu;  // rounds of workgroups over the chip
+    const int ups = (units + strips - 1) / strips;
+    const int ntiles = (ups + GS_MAX_NT - 1) / GS_MAX_NT;
+    const double nt = (double)ups / ntiles;
+    const int steps = (k_steps + splits - 1) / splits;
+    double clocks = (double)waves * ntiles * (steps * (256.0 * nt + 350.0) + 20000.0);
+    if (splits > 1) clocks += (double)M * units * 32.0 * (4.0 * splits + 4.0) / 2.0e12 * 1.4e9;
+    return clocks;
+}
+
+int choose_splitk(const rs_ctx* c, int M, int units, int k_steps) {
+    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_steps));
+    int best = 1;
+    double best_cost = gemm_cost_clocks(c, M, units, k_steps, 1);
+    for (int s = 2; s <= 4 && k_steps / s >= 8; ++s) {
+        const double cost = gemm_cost_clocks(c, M, units, k_steps, s);
+        if (cost < 0.97 * best_cost) {
+            best = s;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 struct WorkspaceLayout {
@@ -160,7 +182,7 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf1
     a.partial = partial;
     a.M = M; a.N = N; a.K = K;
     const float eps = c->cfg.rms_eps;
-    int splits = choose_splitk(c, (M + GS_BM - 1) / GS_BM, N / 32, K / GS_BK);
+    int splits = choose_splitk(c, M, N / 32, K / GS_BK);
     if (splits > 1) {
         const int sps = (K / GS_BK + splits - 1) / splits;
         splits = (K / GS_BK + sps - 1) / sps;
