@@ -52,11 +52,11 @@ typedef enum rs_status {
 
 /* Shape of one decoder layer and the limits of one call. */
 typedef struct rs_layer_cfg {
-    int hidden;               /* H; multiple of 256 */
+    int hidden;               /* H; multiple of 64 */
     int n_q_heads;            /* Hq */
     int n_kv_heads;           /* Hkv; divides Hq */
     int head_dim;             /* d; 64 or 128 */
-    int mlp_inter;            /* I; multiple of 128 */
+    int mlp_inter;            /* I; multiple of 64 */
     float rms_eps;            /* added to mean(x^2) inside the square root */
     float rope_theta;         /* RoPE base; angle of pair j at position n is n * theta^(-2j/d) */
     int qkv_bias;             /* nonzero: rs_layer_weights.b_qkv is used */

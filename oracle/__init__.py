@@ -1,4 +1,4 @@
-"""CPU fp64 oracle of the chunked-prefill decoder layer.
+"""CPU fp64 oracle of the chunked-prefill decoder layer, and a plain statement of the request scheduler.
 
 TEST INFRASTRUCTURE ONLY.  Nothing in the product path (the HIP library and its
 Python binding) may import, call or link this package; it exists so that tests,
@@ -10,3 +10,4 @@ from .decoder_layer import (  # noqa: F401
     layer_forward, layer_forward_rows, ChunkedPrefill, prefill_batch, rel_fro,
 )
 from .brute_force import attention_loops  # noqa: F401
+from .scheduler import TrackedRequest, encoder_batches, schedule_round  # noqa: F401

@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "librserve_prefill.so"
@@ -23,6 +23,12 @@ EXPORTED_SYMBOLS = (
     "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
     "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_last_error", "rs_version",
     "rs_profile_enable", "rs_profile_read",
+)
+
+SCHED_SYMBOLS = (
+    "rs_sched_create", "rs_sched_destroy", "rs_sched_add_request", "rs_sched_mark_ready", "rs_sched_schedulable_tokens",
+    "rs_sched_prompt_length", "rs_sched_prefilled_tokens", "rs_sched_encoder_batches", "rs_sched_next_round",
+    "rs_sched_queue_length", "rs_sched_queue_ids", "rs_sched_release_request",
 )
 
 STEPS = ("row_rms", "qkv_gemm", "append_kv", "attention", "o_gemm", "gate_up_gemm", "down_gemm")
@@ -39,6 +45,18 @@ class _Cfg(C.Structure):
     _fields_ = [("hidden", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
                 ("mlp_inter", C.c_int), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qkv_bias", C.c_int),
                 ("max_tokens_per_call", C.c_int), ("max_requests", C.c_int), ("max_pos", C.c_int)]
+
+
+class _Segment(C.Structure):
+    _fields_ = [("is_mm", C.c_int), ("n_tokens", C.c_int)]
+
+
+class _RoundEntry(C.Structure):
+    _fields_ = [("request_id", C.c_int64), ("first_token", C.c_int), ("n_tokens", C.c_int), ("finished", C.c_int)]
+
+
+class _EncodeBatch(C.Structure):
+    _fields_ = [("first_segment", C.c_int), ("last_segment", C.c_int), ("n_items", C.c_int), ("n_tokens", C.c_int)]
 
 
 class _Weights(C.Structure):
@@ -84,6 +102,18 @@ def load_library():
         "rs_version": (i, []),
         "rs_profile_enable": (i, [vp, i, i]),
         "rs_profile_read": (i, [vp, C.POINTER(C.c_double), C.POINTER(i)]),
+        "rs_sched_create": (i, [i, C.POINTER(vp)]),
+        "rs_sched_destroy": (None, [vp]),
+        "rs_sched_add_request": (i, [vp, C.c_int64, C.POINTER(_Segment), i]),
+        "rs_sched_mark_ready": (i, [vp, C.c_int64, i]),
+        "rs_sched_schedulable_tokens": (i, [vp, C.c_int64]),
+        "rs_sched_prompt_length": (i, [vp, C.c_int64]),
+        "rs_sched_prefilled_tokens": (i, [vp, C.c_int64]),
+        "rs_sched_encoder_batches": (i, [vp, C.c_int64, i, C.POINTER(_EncodeBatch), i, C.POINTER(i)]),
+        "rs_sched_next_round": (i, [vp, C.POINTER(_RoundEntry), i, C.POINTER(i)]),
+        "rs_sched_queue_length": (i, [vp]),
+        "rs_sched_queue_ids": (i, [vp, C.POINTER(C.c_int64), i, C.POINTER(i)]),
+        "rs_sched_release_request": (i, [vp, C.c_int64]),
     }
     for name, (res, args) in proto.items():
         fn = getattr(lib, name)
@@ -266,3 +296,60 @@ class Context:
         _check(self.lib.rs_prefill_batch(self.handle, C.byref(packed.struct), layer, arr_kv, arr_len, r, _ptr(x), _ptr(y),
                                          _ptr(workspace), workspace.numel(), _stream_handle(stream)))
         return y
+
+
+class Scheduler:
+    """rs_sched: embedding tracker + Algorithm 1 encoder batching + Algorithm 2 token scheduling (host only)."""
+
+    def __init__(self, token_budget: int):
+        self._lib = load_library()
+        h = C.c_void_p()
+        _check(self._lib.rs_sched_create(int(token_budget), C.byref(h)))
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._lib.rs_sched_destroy(self._h)
+            self._h = None
+
+    def add_request(self, request_id: int, segments: Sequence[Tuple[bool, int]]):
+        arr = (_Segment * max(len(segments), 1))(*[_Segment(int(bool(m)), int(n)) for m, n in segments])
+        _check(self._lib.rs_sched_add_request(self._h, request_id, arr, len(segments)))
+
+    def mark_ready(self, request_id: int, segment: int):
+        _check(self._lib.rs_sched_mark_ready(self._h, request_id, segment))
+
+    def schedulable_tokens(self, request_id: int) -> int:
+        return self._lib.rs_sched_schedulable_tokens(self._h, request_id)
+
+    def prompt_length(self, request_id: int) -> int:
+        return self._lib.rs_sched_prompt_length(self._h, request_id)
+
+    def prefilled_tokens(self, request_id: int) -> int:
+        return self._lib.rs_sched_prefilled_tokens(self._h, request_id)
+
+    def encoder_batches(self, request_id: int, min_tokens: int, capacity: int = 4096) -> List[Tuple[int, int, int, int]]:
+        out = (_EncodeBatch * max(capacity, 1))()
+        n = C.c_int()
+        _check(self._lib.rs_sched_encoder_batches(self._h, request_id, min_tokens, out, capacity, C.byref(n)))
+        return [(b.first_segment, b.last_segment, b.n_items, b.n_tokens) for b in out[: n.value]]
+
+    def next_round(self, capacity: Optional[int] = None) -> List[Tuple[int, int, int, bool]]:
+        cap = self.queue_length() if capacity is None else capacity
+        out = (_RoundEntry * max(cap, 1))()
+        n = C.c_int()
+        _check(self._lib.rs_sched_next_round(self._h, out, cap, C.byref(n)))
+        return [(e.request_id, e.first_token, e.n_tokens, bool(e.finished)) for e in out[: n.value]]
+
+    def queue_length(self) -> int:
+        return self._lib.rs_sched_queue_length(self._h)
+
+    def queue_ids(self) -> List[int]:
+        cap = self.queue_length()
+        out = (C.c_int64 * max(cap, 1))()
+        n = C.c_int()
+        _check(self._lib.rs_sched_queue_ids(self._h, out, cap, C.byref(n)))
+        return list(out[: n.value])
+
+    def release_request(self, request_id: int):
+        _check(self._lib.rs_sched_release_request(self._h, request_id))

@@ -6,7 +6,8 @@ import subprocess
 import sys
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(PKG_DIR, "csrc", "rserve_prefill.hip")
+SRCS = [os.path.join(PKG_DIR, "csrc", "rserve_prefill.hip"),   # kernels + the prefill ABI
+        os.path.join(PKG_DIR, "csrc", "rserve_sched.cpp")]     # host-only scheduler / tracker ABI
 LIB = os.path.join(PKG_DIR, "librserve_prefill.so")
 
 HIPCC_FLAGS = [
@@ -19,7 +20,7 @@ HIPCC_FLAGS = [
 def build(verbose: bool = True) -> str:
     """Cross-compiles csrc/ into librserve_prefill.so (no GPU needed) and returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [SRC, "-o", LIB + ".tmp"]
+    cmd = [hipcc] + HIPCC_FLAGS + SRCS + ["-o", LIB + ".tmp"]
     if verbose:
         print("[build]", " ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

@@ -150,16 +150,19 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
             const char* vs = ks + TILE_BYTES;
             f32x16 s[2];
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
+            for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[mi][r] = 0.0f;
+            // the two 32-key halves are independent accumulation chains: alternate them so that no MFMA waits for
+            // the result of the one issued just before it
 #pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk) {
+            for (int kk = 0; kk < KSTEPS; ++kk)
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
                     const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
                     bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_row_off[mi] + c);
                     s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mi], 0, 0, 0);
                 }
-            }
             // register r of s[mi] holds key  key0 + mi*32 + 16*(r>>3) + 8*half + (r&7)
             if (key0 + ATT_KEYS - 1 > wpos_lo) {  // tile straddles the causal boundary of some query here
 #pragma unroll
@@ -200,12 +203,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
                     pf[mi * 2 + (r >> 3)][r & 7] = f32_to_bf16(p);
                 }
             l_run += psum;
+            // the DT output tiles are independent chains: walk the keys in the outer loop
 #pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                const uint32_t vrow = (uint32_t)(t * 32 + l32) * 128u;
+            for (int ksx = 0; ksx < 4; ++ksx) {
+                const uint32_t c = ((uint32_t)(ksx * 2 + half) ^ v_swz) * 16u;
 #pragma unroll
-                for (int ksx = 0; ksx < 4; ++ksx) {
-                    const uint32_t c = ((uint32_t)(ksx * 2 + half) ^ v_swz) * 16u;
+                for (int t = 0; t < DT; ++t) {
+                    const uint32_t vrow = (uint32_t)(t * 32 + l32) * 128u;
                     bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + vrow + c);
                     acc_o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ksx], acc_o[t], 0, 0, 0);
                 }

@@ -17,18 +17,23 @@
 #include "common.h"
 #include "elementwise.h"
 #include "gemm_strip.h"
+#include "last_error.h"
 
 namespace {
 
 thread_local std::string g_last_error = "";
 
-rs_status fail(rs_status st, const char* fmt, ...) {
+void set_last_error(const char* fmt, va_list ap) {
     char buf[512];
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    g_last_error = buf;
+}
+
+rs_status fail(rs_status st, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(buf, sizeof(buf), fmt, ap);
+    set_last_error(fmt, ap);
     va_end(ap);
-    g_last_error = buf;
     return st;
 }
 
@@ -44,6 +49,14 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 constexpr int RING_SLOTS = 32;
 
 }  // namespace
+
+rs_status rs_internal_fail(rs_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    set_last_error(fmt, ap);
+    va_end(ap);
+    return st;
+}
 
 struct rs_ctx {
     rs_layer_cfg cfg;

@@ -23,11 +23,13 @@ def lib():
     return binding.load_library()
 
 
-def test_header_symbols_are_exported(lib):
-    header = open(os.path.join(ROOT, "include", "rserve_prefill.h")).read()
+@pytest.mark.parametrize("header_name, symbols", [("rserve_prefill.h", binding.EXPORTED_SYMBOLS),
+                                                  ("rserve_sched.h", binding.SCHED_SYMBOLS)])
+def test_header_symbols_are_exported(lib, header_name, symbols):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rs_[a-z_0-9]+)\s*\(", header))
-    assert declared == set(binding.EXPORTED_SYMBOLS)
+    assert declared == set(symbols)
     for name in declared:
         assert hasattr(lib, name), name
     assert lib.rs_version() == 1

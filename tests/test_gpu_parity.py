@@ -224,6 +224,56 @@ def test_small_ragged_batch_with_empty_and_single_row_requests():
         off += t
 
 
+def test_scheduled_multi_request_prefill_matches_unchunked_oracle():
+    """Algorithm 2 end to end: requests with multimodal items whose embeddings arrive in a random order are prefilled
+    through rs_sched_next_round + rs_prefill_batch under a token budget, two layers deep; whatever chunks the scheduler
+    cut, every request must equal the oracle's unchunked prefill of its prompt (section 2.2.1)."""
+    from paper_2509_24381_amd.binding import Scheduler
+    R = _runner()
+    shape = synth.TINY
+    ws = [synth.layer_weights(shape, 300 + l, gains="uniform") for l in range(2)]
+    rng = np.random.default_rng(301)
+    budget = 96
+    stack = R.LayerStack(shape, ws, max_tokens=budget, max_requests=8, max_pos=512)
+    sched = Scheduler(budget)
+    reqs = {}
+    for rid in range(5):
+        segs = [(bool(rng.integers(0, 2)), int(rng.integers(1, 70))) for _ in range(int(rng.integers(2, 6)))]
+        rows = synth.prompt_rows([("image" if mm else "text", n) for mm, n in segs], shape.hidden, 310 + rid)
+        reqs[rid] = (segs, rows)
+    emb = {rid: _dev(rows) for rid, (segs, rows) in reqs.items()}
+    out = {rid: torch.zeros_like(e) for rid, e in emb.items()}
+    kvs = {rid: stack.new_cache(rows.shape[0]) for rid, (segs, rows) in reqs.items()}
+    encoder_queue = [(rid, k) for rid, (segs, _) in reqs.items() for k, (mm, _) in enumerate(segs) if mm]
+    rng.shuffle(encoder_queue)
+    arrivals = list(reqs)
+    arrived = set()
+    rounds = 0
+    while arrivals or encoder_queue or sched.queue_length():
+        rounds += 1
+        assert rounds < 500
+        if arrivals:
+            rid = arrivals.pop(0)
+            sched.add_request(rid, reqs[rid][0])
+            arrived.add(rid)
+        if encoder_queue and encoder_queue[-1][0] in arrived and rng.random() < 0.7:
+            rid, k = encoder_queue.pop()
+            sched.mark_ready(rid, k)
+        entries = sched.next_round()
+        assert sum(n for _, _, n, _ in entries) <= budget
+        R.run_scheduled_round(stack, entries, emb, kvs, out)
+    torch.cuda.synchronize()
+    for rid, (segs, rows) in reqs.items():
+        cur = rows
+        for l in range(2):
+            y_ref, k_ref, v_ref = layer_forward(cur, LayerParams.from_arrays(shape, ws[l]))
+            k, v = kvs[rid].export(l)
+            check(f"scheduled req {rid} layer {l} K", _np(k), k_ref, tol=TOL * (1 + l))
+            check(f"scheduled req {rid} layer {l} V", _np(v), v_ref, tol=TOL * (1 + l))
+            cur = y_ref
+        check(f"scheduled req {rid} Y", _np(out[rid]), cur, tol=2 * TOL)
+
+
 # ------------------------------------------------------------------ production shapes
 def test_workload2_7b_2048_budget512():
     wl = synth.workload(2)
