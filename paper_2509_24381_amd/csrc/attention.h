@@ -239,3 +239,287 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
             }
     }
 }
+
+
+// ------------------------------------------------------------------------------------------------------------------
+// Software-pipelined variant of the same computation.  Per key tile a wavefront has two kinds of work: 32 MFMAs (the two
+// products) and the online softmax on the vector ALU (an exponential per score at a quarter of the ALU rate, plus the
+// scaling, the running maximum, the row sum and the bf16 conversion), about equally long; run one after the other, the
+// matrix pipe idles half of the time.  Here the score product of tile kb+1 is issued between the exponentials of tile
+// kb, and the running maximum of tile kb+1 is formed behind the MFMAs of the P.V product of tile kb, so each pipe works
+// in the shadow of the other.  K therefore runs one tile ahead of V: iteration kb reads K(kb+1) and V(kb) from LDS while
+// K(kb+2) and V(kb+1) travel global -> LDS by DMA (buffer_load ... lds: no staging registers) into the buffers that
+// iteration kb-1 finished with.  The four buffers are separate LDS objects so that the compiler can tell that the
+// fragment reads of an iteration do not touch the buffers being filled; it waits for the DMA at the barrier that ends
+// the iteration.
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const ReqDesc* __restrict__ reqs,
+                                                                        const AttnItem* __restrict__ items,
+                                                                        const bf16* __restrict__ qkv, int ld_qkv,
+                                                                        bf16* __restrict__ out, int ld_out,
+                                                                        int g, float scale_log2e) {
+    constexpr int KSTEPS = D / 16;
+    constexpr int DT = D / 32;
+    constexpr int K_ROW_BYTES = D * 2;
+    constexpr int K_CPR = K_ROW_BYTES / 16;
+    constexpr int TILE_BYTES = ATT_KEYS * D * 2;
+    constexpr int LOADS = TILE_BYTES / (256 * 16);
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    __shared__ __attribute__((aligned(16))) char k_buf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) char k_buf1[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) char v_buf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) char v_buf1[TILE_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+
+    const AttnItem item = items[blockIdx.x];
+    const ReqDesc rq = reqs[item.req];
+    const int cap = rq.cap;
+    const int rows_total = rq.T * g;
+    const int row = item.qblock * ATT_ROWS + wave * 32 + l32;
+    const int row_c = min(row, rows_total - 1);
+    const int tok = row_c / g;
+    const int head = item.kvh * g + (row_c - tok * g);
+    const int qpos = rq.P + tok;
+    const int wrow_lo = min(item.qblock * ATT_ROWS + wave * 32, rows_total - 1);
+    const int wpos_lo = rq.P + wrow_lo / g;  // every query of this wavefront sees all keys <= wpos_lo
+
+    bf16x8 qf[KSTEPS];
+    {
+        const bf16* qp = qkv + (size_t)(rq.row0 + tok) * ld_qkv + head * D + half * 8;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+    }
+
+    // ---- tile loader: a tile is a contiguous TILE_BYTES run of this KV head's cache; load instruction i of a wavefront
+    //      fills LDS bytes [(i*256 + wave*64)*16, +1 KB) linearly by lane, each lane fetching the 16-byte chunk that
+    //      belongs in its (swizzled) place.  Tiles past the item's last one are not fetched.
+    const int nkb = item.nkb;
+    const int head_bytes = cap * D * 2;  // one KV head's K (or V^T) region
+    char* const k_head = reinterpret_cast<char*>(rq.kcache) + (size_t)item.kvh * head_bytes;
+    char* const v_head = reinterpret_cast<char*>(rq.vtcache) + (size_t)item.kvh * head_bytes;
+    uint32_t k_src_off[4], v_src_off[4];  // (fixed bound: LOADS <= 4; a template-dependent bound breaks the host-side stub)
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int q = i * 256 + tid;
+        {
+            const int r = q / K_CPR, p = q % K_CPR;
+            const int c = (K_CPR == 16) ? (p ^ (r & 15)) : (p ^ ((r >> 1) & 7));
+            k_src_off[i] = (uint32_t)(r * K_ROW_BYTES + c * 16);
+        }
+        {
+            const int r = q >> 3, p = q & 7;
+            const int c = p ^ ((r >> 1) & 7);
+            v_src_off[i] = (uint32_t)(r * 128 + c * 16);
+        }
+    }
+    auto fetch_k = [&](char* buf, int kb) {
+        if (kb < nkb) {
+            const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)k_head, 0, head_bytes, 0x00020000);
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, k_src_off[i],
+                                                         kb * TILE_BYTES, 0, 0);
+        }
+    };
+    auto fetch_v = [&](char* buf, int kb) {
+        if (kb < nkb) {
+            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)v_head, 0, head_bytes, 0x00020000);
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, v_src_off[i],
+                                                         kb * TILE_BYTES, 0, 0);
+        }
+    };
+
+    const int pi = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    uint32_t k_row_off[2], k_swz[2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+        const int r = mi * 32 + pi;
+        k_row_off[mi] = (uint32_t)(r * K_ROW_BYTES);
+        k_swz[mi] = (K_CPR == 16) ? (uint32_t)(r & 15) : (uint32_t)((r >> 1) & 7);
+    }
+    const uint32_t v_swz = (uint32_t)((lane >> 1) & 7);
+
+    f32x16 acc_o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.0f;
+    float m_run = -INFINITY;  // running max of the raw scores of this lane's query (shared by both half-waves)
+    float l_run = 0.0f;       // running sum over THIS half-wave's keys
+    float alpha = 1.0f;       // factor the accumulated output still has to be multiplied by before the next P.V
+    bool rescale = false;     // some query of this wavefront saw its maximum grow (wave-uniform)
+
+    // raw scores of one tile: register r of s[mi] holds key  key0 + mi*32 + 16*(r>>3) + 8*half + (r&7)
+    auto zero_scores = [&](f32x16 (&s)[2]) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[mi][r] = 0.0f;
+    };
+    auto score_mfma = [&](f32x16 (&s)[2], const char* ks, int kk, int mi) {
+        const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
+        bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_row_off[mi] + c);
+        s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mi], 0, 0, 0);
+    };
+    // mask and running maximum of one tile's scores; leaves m_run updated and alpha / rescale for the output
+    auto tile_max = [&](f32x16 (&s)[2], int key0) {
+        if (key0 + ATT_KEYS - 1 > wpos_lo) {  // some query of this wavefront does not see the whole tile
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + mi * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+                    s[mi][r] = (key <= qpos) ? s[mi][r] : -INFINITY;
+                }
+        }
+        float mloc = s[0][0];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) mloc = fmaxf(fmaxf(s[mi][r], s[mi][r + 1]), mloc);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, WAVE));
+        const float m_new = fmaxf(m_run, mloc);  // finite from the first tile on: key 0 is visible to every query
+        rescale = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
+        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+        m_run = m_new;
+    };
+
+    // ---- prologue: K(0), V(0), K(1) into LDS; scores and maximum of tile 0
+    fetch_k(k_buf0, 0);
+    fetch_v(v_buf0, 0);
+    fetch_k(k_buf1, 1);
+    __syncthreads();
+    f32x16 sA[2], sB[2];
+    zero_scores(sA);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) score_mfma(sA, k_buf0, kk, mi);
+    tile_max(sA, 0);
+    __syncthreads();  // every wavefront is done with K(0): iteration 0 may overwrite it
+
+    // one iteration: scur = raw scores of tile kb (masked, maximum known); snext receives those of tile kb+1.
+    // k_next holds K(kb+1), v_cur V(kb); k_fill (= K(kb)'s buffer) receives K(kb+2), v_fill (= V(kb-1)'s) V(kb+1).
+    auto iteration = [&](int kb, f32x16 (&scur)[2], f32x16 (&snext)[2], const char* k_next, char* k_fill, const char* v_cur,
+                         char* v_fill) {
+        fetch_k(k_fill, kb + 2);
+        fetch_v(v_fill, kb + 1);
+        const float mb = m_run * scale_log2e;
+        // ---- phase 1: P(kb) = exp2(S(kb) c - m c), its row sum and bf16 form.  Behind each of the 2*KSTEPS score MFMAs of
+        //      tile kb+1 go the exponentials of 32 / (2*KSTEPS) scores of tile kb; scheduling fences keep that order, and
+        //      each K fragment is read from LDS one group ahead of the MFMA that uses it.
+        zero_scores(snext);
+        bf16x8 pf[4];
+        float psum = 0.0f;
+        constexpr int NS = 2 * KSTEPS;   // score MFMAs per tile
+        constexpr int PER = 32 / NS;     // scores of tile kb handled behind each of them (2 for d = 128, 4 for d = 64)
+        auto k_frag = [&](int step) {
+            const int kk = step >> 1, mi = step & 1;
+            const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
+            return *reinterpret_cast<const bf16x8*>(k_next + k_row_off[mi] + c);
+        };
+        bf16x8 kf = k_frag(0);
+#pragma unroll
+        for (int step = 0; step < NS; ++step) {
+            const bf16x8 kf_next = k_frag(step + 1 < NS ? step + 1 : step);
+            __builtin_amdgcn_sched_barrier(0);  // the read goes out first: its latency hides behind this group's work
+            snext[step & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[step >> 1], snext[step & 1], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < PER; e += 2) {
+                const int idx = step * PER + e, mi = idx >> 4, r = idx & 15;
+                // raw v_exp_f32: arguments are <= 0, results below the normal range may flush to zero
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[mi][r], scale_log2e, -mb));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[mi][r + 1], scale_log2e, -mb));
+                const bf16x2 pp = {f32_to_bf16(p0), f32_to_bf16(p1)};
+                const bf16x2 ones = {f32_to_bf16(1.0f), f32_to_bf16(1.0f)};
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);  // the row sum adds what the product will use
+                pf[mi * 2 + (r >> 3)][r & 7] = pp[0];
+                pf[mi * 2 + (r >> 3)][(r & 7) + 1] = pp[1];
+            }
+            asm volatile("" : "+v"(psum));  // pins this group's vector work here (it would otherwise sink below the MFMAs)
+            kf = kf_next;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- the accumulated output catches up with the maximum of tile kb
+        l_run = l_run * alpha + psum;
+        if (rescale) {
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+        }
+        // ---- phase 2: O += V(kb)^T P(kb); behind the MFMAs, the mask and the running maximum of tile kb+1
+        const int key1 = (kb + 1) * ATT_KEYS;
+        const bool more = kb + 1 < nkb;
+        if (more && key1 + ATT_KEYS - 1 > wpos_lo) {  // some query of this wavefront does not see the whole next tile
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key1 + mi * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+                    snext[mi][r] = (key <= qpos) ? snext[mi][r] : -INFINITY;
+                }
+        }
+        auto v_frag = [&](int step) {
+            const int ksx = step / DT, t = step % DT;
+            const uint32_t c = ((uint32_t)(ksx * 2 + half) ^ v_swz) * 16u;
+            return *reinterpret_cast<const bf16x8*>(v_cur + (uint32_t)(t * 32 + l32) * 128u + c);
+        };
+        constexpr int NV = 4 * DT;       // P.V MFMAs per tile
+        constexpr int MPER = 32 / NV;    // scores of tile kb+1 folded into the maximum behind each of them
+        float mloc = snext[0][0];
+        bf16x8 vf = v_frag(0);
+#pragma unroll
+        for (int step = 0; step < NV; ++step) {
+            const bf16x8 vf_next = v_frag(step + 1 < NV ? step + 1 : step);
+            __builtin_amdgcn_sched_barrier(0);
+            acc_o[step % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[step / DT], acc_o[step % DT], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < MPER; e += 2) {
+                const int idx = step * MPER + e, mi = idx >> 4, r = idx & 15;
+                mloc = fmaxf(fmaxf(snext[mi][r], snext[mi][r + 1]), mloc);
+            }
+            asm volatile("" : "+v"(mloc));
+            vf = vf_next;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) {
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, WAVE));
+            const float m_new = fmaxf(m_run, mloc);  // finite from the first tile on: key 0 is visible to every query
+            rescale = __builtin_amdgcn_ballot_w64(m_new > m_run) != 0;
+            alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+            m_run = m_new;
+        }
+        __syncthreads();
+    };
+
+    int kb = 0;
+    for (; kb + 1 < nkb; kb += 2) {
+        iteration(kb, sA, sB, k_buf1, k_buf0, v_buf0, v_buf1);
+        iteration(kb + 1, sB, sA, k_buf0, k_buf1, v_buf1, v_buf0);
+    }
+    if (kb < nkb) iteration(kb, sA, sB, k_buf1, k_buf0, v_buf0, v_buf1);
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
+    if (row < rows_total) {
+        const float inv = 1.0f / l_tot;
+        const uint32_t m = (uint32_t)(rq.row0 + tok);
+        char* op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u + half * 8;
+        const int ks0 = (head * D) >> 4;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc_o[t][4 * q + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o;
+            }
+    }
+}
+

@@ -69,6 +69,7 @@ struct rs_ctx {
     size_t slot_bytes = 0;
     int next_slot = 0;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
+    int attn_variant = 1;     // RS_ATTN environment variable: 1 software-pipelined attention kernel, 0 the plain one
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
     // measurement hook: HIP events around every launch of one step of the layer
@@ -245,8 +246,12 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     tm.end(RS_STEP_APPEND_KV);
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
     tm.begin(RS_STEP_ATTENTION);
-    hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
-                       (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+    if (c->attn_variant == 1)
+        hipLaunchKernelGGL(attn_prefill_pipelined_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+    else
+        hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     RS_HIP(hipGetLastError());
     tm.end(RS_STEP_ATTENTION);
     return RS_OK;
@@ -447,6 +452,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->cfg = f;
     c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
+    if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
     c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;
@@ -493,6 +499,9 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
+    // (the pipelined attention kernel keeps its LDS in static arrays; these references make the launch stubs exist)
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
     *out = c;
     return RS_OK;
