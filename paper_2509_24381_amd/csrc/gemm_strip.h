@@ -93,6 +93,17 @@ RS_DEVICE uint32_t frag_offset_bytes(uint32_t m, uint32_t n, uint32_t width) {
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
+// The two half-waves of an MFMA result hold alternate runs of 4 features of the same token: lanes 0..31 features
+// 8q..8q+3, lanes 32..63 features 8q+4..8q+7.  Given the runs of two neighbouring 8-feature groups (even, odd), one
+// v_permlane32_swap per dword hands the lower lanes the whole even group and the upper lanes the whole odd group, so every
+// lane stores one complete 16-byte chunk (whole cache lines per store instead of interleaved 8-byte halves).
+RS_DEVICE u32x4 pair_runs(bf16x4 even_run, bf16x4 odd_run) {
+    const u32x2 a = __builtin_bit_cast(u32x2, even_run), b = __builtin_bit_cast(u32x2, odd_run);
+    const u32x2 s0 = __builtin_amdgcn_permlane32_swap(a[0], b[0], false, false);  // upper lanes of a <-> lower lanes of b
+    const u32x2 s1 = __builtin_amdgcn_permlane32_swap(a[1], b[1], false, false);
+    return u32x4{s0[0], s1[0], s0[1], s1[1]};
+}
+
 // Lane-local epilogue of one tile.  acc[i][j][r] holds token m = m_base + j*32 + l32 and row 8*(r>>2) + 4*half + (r&3) of
 // unit unit0 + i.  Per-row inputs and all outputs go through buffer resources sized to M rows, so lanes whose token lies
 // past M read zeros and store nothing without any divergent branch (a divergent branch here, inside the tile loop, makes
@@ -110,18 +121,18 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, m_pad * a.ldo * 2, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t r_sc = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_scale, 0, a.M * 4, RSRC_FLAGS);
             const float sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r_sc, m * 4, 0, 0));
-            const uint32_t oblk = (uint32_t)(m >> 5) * (uint32_t)(a.ldo >> 4) * 1024u + (uint32_t)l32 * 16u + (uint32_t)half * 8u;
+            const uint32_t oblk = (uint32_t)(m >> 5) * (uint32_t)(a.ldo >> 4) * 1024u + (uint32_t)l32 * 16u + (uint32_t)half * 512u;
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+            for (int i = 0; i < NT; ++i) {
+                bf16x4 o[2];
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    bf16x4 o;
+                for (int q = 0; q < 2; ++q)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        o[e] = f32_to_bf16(silu_f32(acc[i][j][4 * q + e] * sc) * (acc[i][j][8 + 4 * q + e] * sc));
-                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out,
-                                                          oblk + (uint32_t)((unit0 + i) * 2 + q) * 512u, 0, 0);
-                }
+                        o[q][e] = f32_to_bf16(silu_f32(acc[i][j][4 * q + e] * sc) * (acc[i][j][8 + 4 * q + e] * sc));
+                // lower lanes: features 16u..16u+7 (first half of the k-step), upper lanes: 16u+8..16u+15 (second half)
+                __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[0], o[1]), r_out, oblk + (uint32_t)(unit0 + i) * 1024u, 0, 0);
+            }
         } else if constexpr (EPI == EPI_QKV_ROPE) {
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t r_sc = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_scale, 0, a.M * 4, RSRC_FLAGS);
@@ -140,6 +151,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     const int uh = gu & ((1 << uph_shift) - 1);
                     const int fl = (gu >> uph_shift) * a.head_dim + uh * 16 + 4 * half;  // column of this lane's first "low" run
                     const float2* cs = csr + uh * 16 + 4 * half;
+                    bf16x4 olq[2], ohq[2];
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         float bl[4] = {0.0f, 0.0f, 0.0f, 0.0f}, bh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -161,10 +173,15 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                             ol[e] = f32_to_bf16(lo * c.x - hi * c.y);
                             oh[e] = f32_to_bf16(hi * c.x + lo * c.y);
                         }
-                        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, ol), r_out, orow + (uint32_t)(fl + 8 * q) * 2u, 0, 0);
-                        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, oh), r_out, orow + (uint32_t)(fl + hd2 + 8 * q) * 2u, 0, 0);
+                        olq[q] = ol;
+                        ohq[q] = oh;
                     }
+                    // lower lanes store features 0..7 of the unit's 16, upper lanes 8..15, as whole 16-byte chunks
+                    const uint32_t col = (uint32_t)((gu >> uph_shift) * a.head_dim + uh * 16 + 8 * half);
+                    __builtin_amdgcn_raw_buffer_store_b128(pair_runs(olq[0], olq[1]), r_out, orow + col * 2u, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(pair_runs(ohq[0], ohq[1]), r_out, orow + (col + (uint32_t)hd2) * 2u, 0, 0);
                 } else {
+                    bf16x4 o[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int n = gu * 32 + 8 * q + 4 * half;
@@ -174,11 +191,13 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
 #pragma unroll
                             for (int e = 0; e < 4; ++e) b[e] = bf16_to_f32(b4[e]);
                         }
-                        bf16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc[i][j][4 * q + e] * sc + b[e]);
-                        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out, orow + (uint32_t)n * 2u, 0, 0);
+                        for (int e = 0; e < 4; ++e) o[q][e] = f32_to_bf16(acc[i][j][4 * q + e] * sc + b[e]);
                     }
+#pragma unroll
+                    for (int pr = 0; pr < 2; ++pr)
+                        __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[2 * pr], o[2 * pr + 1]), r_out,
+                                                               orow + (uint32_t)(gu * 32 + 16 * pr + 8 * half) * 2u, 0, 0);
                 }
             }
         } else if constexpr (EPI == EPI_PARTIAL) {
@@ -204,20 +223,24 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 float ss = 0.0f;
+                bf16x4 o[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const uint32_t n = (uint32_t)((unit0 + i) * 32 + 8 * q + 4 * half);
                     const uint32_t roff = a.resid_frag ? frag_offset_bytes(m, n, a.ldr) : ((uint32_t)m * (uint32_t)a.ldr + n) * 2u;
-                    const uint32_t ooff = a.out_frag ? frag_offset_bytes(m, n, a.ldo) : ((uint32_t)m * (uint32_t)a.ldo + n) * 2u;
                     const bf16x4 r4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_raw_buffer_load_b64(r_res, roff, 0, 0));
-                    bf16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        o[e] = f32_to_bf16(acc[i][j][4 * q + e] + bf16_to_f32(r4[e]));
-                        const float st = bf16_to_f32(o[e]);
+                        o[q][e] = f32_to_bf16(acc[i][j][4 * q + e] + bf16_to_f32(r4[e]));
+                        const float st = bf16_to_f32(o[q][e]);
                         ss += st * st;
                     }
-                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), r_out, ooff, 0, 0);
+                }
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {  // lower lanes store the even 8-feature group of the pair, upper lanes the odd one
+                    const uint32_t n = (uint32_t)((unit0 + i) * 32 + 16 * pr + 8 * half);
+                    const uint32_t ooff = a.out_frag ? frag_offset_bytes(m, n, a.ldo) : ((uint32_t)m * (uint32_t)a.ldo + n) * 2u;
+                    __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[2 * pr], o[2 * pr + 1]), r_out, ooff, 0, 0);
                 }
                 // the two half-waves hold the two halves of this token's 32 features of the unit; half 0 stores the sum
                 // (an empty resource when no sums are wanted; half 1 and rows past M aim outside it)
