@@ -1,43 +1,44 @@
-// HBM-bound helper kernels: RMSNorm row factors, K / V append (V transposing), weight packing, cache export/import.
+// HBM-bound helper kernels: RMSNorm row factors and input repack, K / V append (V transposing), weight packing, cache
+// export/import.
 #pragma once
 #include "attention.h"
 #include "common.h"
 
-// ---------------------------------------------------------------- RMSNorm row factor: one wavefront per row
-// inv_rms[row] = rsqrt(mean(x[row]^2) + eps), sums in fp32.  The factor is applied inside the next GEMM's epilogue.
-__global__ __launch_bounds__(256) void row_inv_rms_kernel(const bf16* __restrict__ x, float* __restrict__ inv_rms,
-                                                          int rows, int H, float eps) {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const bf16* xr = x + (size_t)row * H;
+// ---------------------------------------------------------------- layer input: RMSNorm row factor + fragment-major copy
+// One pass over x: inv_rms[row] = rsqrt(mean(x[row]^2) + eps) (fp32 sums; the factor is applied inside the next GEMM's
+// epilogue), and dst receives x in the GEMMs' token-operand layout: blocks of 32 tokens x 16 features, the two 8-feature
+// halves 512 bytes apart, tokens 16 bytes apart (rows of the last block past `rows` are left untouched: they are never
+// used).  One workgroup handles 8 tokens: 32 threads read 512 contiguous bytes of one token per step, and the 8 tokens'
+// 16-byte chunks of one (k-step, half) land in 128 contiguous bytes (one cache line).
+__global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16* __restrict__ x, bf16* __restrict__ dst,
+                                                                     float* __restrict__ inv_rms, int rows, int H, float eps) {
+    const int r = threadIdx.x >> 5, c = threadIdx.x & 31;
+    const int m = blockIdx.x * 8 + r;
+    const int mc = min(m, rows - 1);  // threads of rows past the end follow along (their shuffles are needed) and store nothing
+    const char* src = reinterpret_cast<const char*>(x + (size_t)mc * H) + c * 16;
+    char* out = reinterpret_cast<char*>(dst) + ((size_t)(m >> 5) * (H >> 4) * 2 + c) * 512 + (m & 31) * 16;
     float ss = 0.0f;
-    for (int c = lane; c < H / 8; c += WAVE) {
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c * 8);
+    const int chunks = H >> 3;  // 16-byte chunks per row; a step covers 32 of them (256 features = 16 k-steps x 2 halves)
+    for (int c0 = 0; c0 < chunks; c0 += 4 * 32) {
+        uint4 v[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float f = bf16_to_f32(v[e]);
-            ss += f * f;
-        }
+        for (int u = 0; u < 4; ++u)
+            if (c0 + u * 32 + c < chunks) v[u] = ld_global_16(src + (size_t)(c0 + u * 32) * 16);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (c0 + u * 32 + c < chunks) {
+                const bf16x8 h = as_bf16x8(v[u]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float f = bf16_to_f32(h[e]);
+                    ss += f * f;
+                }
+                if (m < rows) st_global_16(out + (size_t)(c0 + u * 32) * 512, v[u]);
+            }
     }
-    ss = wave_sum(ss);
-    if (lane == 0) inv_rms[row] = rsqrtf(ss / (float)H + eps);
-}
-
-// ---------------------------------------------------------------- row-major -> fragment-major copy of the layer input
-// dst holds x in the GEMMs' token-operand layout: blocks of 32 tokens x 16 features, the two 8-feature halves 512 bytes
-// apart, tokens 16 bytes apart (rows of the last block past `rows` are left untouched: they are never used).  One
-// workgroup moves 32 tokens x 128 features: 8 threads read one token's 256 contiguous bytes, and the 8 tokens of a
-// wavefront's 16-byte chunks of one (k-step, half) land in 128 contiguous bytes.
-__global__ __launch_bounds__(256) void to_fragment_major_kernel(const bf16* __restrict__ x, bf16* __restrict__ dst, int rows, int H) {
-    const int mb = blockIdx.x;
-    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
-    const int m = mb * 32 + r;
-    if (m >= rows) return;
-    const char* src = reinterpret_cast<const char*>(x + (size_t)m * H) + c * 16;
-    char* out = reinterpret_cast<char*>(dst) + ((size_t)mb * (H >> 4) * 2 + c) * 512 + r * 16;
-    for (int k0 = blockIdx.y * 64; k0 < H; k0 += gridDim.y * 64)  // 64 features = 8 chunks = 4 k-steps x 2 halves
-        st_global_16(out + (size_t)(k0 >> 4) * 1024, ld_global_16(src + (size_t)k0 * 2));
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) ss += __shfl_xor(ss, off, WAVE);
+    if (c == 0 && m < rows) inv_rms[m] = rsqrtf(ss / (float)H + eps);
 }
 
 // inv_rms[m] = rsqrt(sum_u rowss[m][u] / H + eps): closes the per-row sums of squares left by the EPI_RESIDUAL epilogue.
@@ -60,13 +61,13 @@ struct KVBlockItem {
 
 // One workgroup per (touched 64-token block, KV head).  The rotated k rows are copied from the qkv buffer to the
 // request's K cache (256-byte rows, 16-byte vector copies).  The v rows are transposed through LDS and written as
-// [d][64] with the token index innermost.  Tokens before P keep their content; V positions at or beyond P+T inside
-// the block are zero-filled.
+// [d][64] with the token index innermost, 16 bytes (8 tokens) per store.  Tokens before P keep their content; V
+// positions at or beyond P+T inside the block are zero-filled.
 template <int D>
 __global__ __launch_bounds__(256) void append_kv_kernel(const bf16* __restrict__ qkv, int ld_qkv,
                                                         const ReqDesc* __restrict__ reqs,
                                                         const KVBlockItem* __restrict__ blocks, int Hq, int Hkv) {
-    __shared__ bf16 tile[64][D + 2];
+    __shared__ __attribute__((aligned(16))) bf16 tile[64][D + 8];  // row stride D*2 + 16 bytes: 16-byte aligned, odd in 16-byte units
     const KVBlockItem it = blocks[blockIdx.x];
     const ReqDesc rq = reqs[it.req];
     const int c = blockIdx.y;
@@ -77,25 +78,33 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const bf16* __restrict__
     for (int idx = threadIdx.x; idx < 64 * CPR; idx += blockDim.x) {
         const int kk = idx / CPR, ch = idx - kk * CPR;
         const int pos = tok0 + kk;
-        if (pos >= rq.P && pos < rq.P + rq.T) {
-            const uint4 v = ld_global_16(qkv + (size_t)(rq.row0 + pos - rq.P) * ld_qkv + k_col + ch * 8);
-            st_global_16(rq.kcache + ((size_t)c * rq.cap + pos) * D + ch * 8, v);
+        const bool live = pos >= rq.P && pos < rq.P + rq.T;
+        uint4 k = make_uint4(0u, 0u, 0u, 0u), v = make_uint4(0u, 0u, 0u, 0u);
+        if (live) {
+            const bf16* row = qkv + (size_t)(rq.row0 + pos - rq.P) * ld_qkv + ch * 8;
+            k = ld_global_16(row + k_col);
+            v = ld_global_16(row + v_col);
+            st_global_16(rq.kcache + ((size_t)c * rq.cap + pos) * D + ch * 8, k);
         }
-    }
-    for (int idx = threadIdx.x; idx < 64 * (D / 2); idx += blockDim.x) {
-        const int kk = idx / (D / 2), dd = (idx - kk * (D / 2)) * 2;
-        const int pos = tok0 + kk;
-        bf16x2 v = {f32_to_bf16(0.0f), f32_to_bf16(0.0f)};
-        if (pos >= rq.P && pos < rq.P + rq.T)
-            v = *reinterpret_cast<const bf16x2*>(qkv + (size_t)(rq.row0 + pos - rq.P) * ld_qkv + v_col + dd);
-        tile[kk][dd] = v[0];
-        tile[kk][dd + 1] = v[1];
+        *reinterpret_cast<uint4*>(&tile[kk][ch * 8]) = v;  // zeros for positions outside [P, P+T)
     }
     __syncthreads();
     bf16* dst = rq.vtcache + ((size_t)c * (rq.cap / 64) + it.block) * D * 64;
-    for (int idx = threadIdx.x; idx < D * 64; idx += blockDim.x) {
-        const int dd = idx >> 6, kk = idx & 63;
-        if (tok0 + kk >= rq.P) dst[dd * 64 + kk] = tile[kk][dd];
+    // thread -> (feature dd, group of 8 tokens): gathers the 8 tokens' values of feature dd and stores them as one chunk
+    for (int idx = threadIdx.x; idx < D * 8; idx += blockDim.x) {
+        const int dd = idx >> 3, g8 = idx & 7;
+        const int t0 = g8 * 8;
+        if (tok0 + t0 + 7 < rq.P) continue;  // all 8 tokens are older than this call: keep them
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = tile[t0 + e][dd];
+        if (tok0 + t0 >= rq.P) {
+            *reinterpret_cast<bf16x8*>(dst + dd * 64 + t0) = o;
+        } else {  // the group straddles P: element-wise, older tokens untouched
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tok0 + t0 + e >= rq.P) dst[dd * 64 + t0 + e] = o[e];
+        }
     }
 }
 

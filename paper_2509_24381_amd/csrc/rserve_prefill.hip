@@ -372,10 +372,8 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
 
     // 1/rms of every input row (the first RMSNorm; its gain lives in the packed W_qkv)
     tm.begin(RS_STEP_ROW_RMS);
-    hipLaunchKernelGGL(row_inv_rms_kernel, dim3((T + 3) / 4), dim3(256), 0, st, xb, inv_rms1, T, H, f.rms_eps);
-    RS_HIP(hipGetLastError());
-    // and x in the GEMMs' fragment-major token-operand layout
-    hipLaunchKernelGGL(to_fragment_major_kernel, dim3((T + 31) / 32, std::min(8, H / 64)), dim3(256), 0, st, xb, xf, T, H);
+    // and, in the same pass, x in the GEMMs' fragment-major token-operand layout
+    hipLaunchKernelGGL(rms_and_fragment_major_kernel, dim3((T + 7) / 8), dim3(256), 0, st, xb, xf, inv_rms1, T, H, f.rms_eps);
     RS_HIP(hipGetLastError());
     tm.end(RS_STEP_ROW_RMS);
     // qkv = rope( (x Wqkv'^T) / rms + b )
