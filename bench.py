@@ -5,6 +5,8 @@ A step is one pass of the whole hot path over the benchmark workload: a syntheti
 (6 images of 1024 embedding rows interleaved with text spans) prefilled in 4 chunks under a 2048-token budget through
 4 stacked 7B-shaped decoder layers, i.e. 16 rs_prefill_chunk calls with the KV prefix growing 0 -> 6144.
 `value` = layer-tokens per second (tokens x layers / time), inputs and weights resident in HBM.
+`--workload 1..5` times one of the other parity workloads the same way (4 = the 16-request ragged micro-batch through
+rs_prefill_batch, 5 = the 72B-shaped layer over a 32768-token prompt); the default, 3, is the headline configuration.
 
 Prints ONE JSON line (see README / DESIGN for the fields): metric, value, ms_per_step, roofline of the dominant
 kernel (the fused gate/up + SwiGLU GEMM, timed live with HIP events on its own stream inside the timed region), and
@@ -70,6 +72,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
+                    help="which of the five synthetic workloads to time (default 3: the headline configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline sample is sized for")
@@ -89,22 +93,46 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = synth.workload(3)
+    wl = synth.workload(args.workload)
     sh = wl.shape
     weights = [wl.weights(l) for l in range(wl.n_layers)]
-    x = wl.prompt()
-    chunks = wl.chunks()
-    stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=1, max_pos=wl.n_tokens)
     w0 = weights[0]
+    if args.workload == 4:
+        # one rs_prefill_batch call per step: 16 requests with imported prior caches, ragged chunks summing to the budget
+        reqs = wl.batch()
+        x = __import__("numpy").concatenate([r.rows for r in reqs], axis=0)
+        lens = [r.rows.shape[0] for r in reqs]
+        priors = [r.prior_len for r in reqs]
+        stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=len(reqs), max_pos=wl.max_prior + wl.budget)
+        kvs = []
+        for r in reqs:
+            kv = stack.new_cache(wl.max_prior + wl.budget)
+            if r.prior_len:
+                kv.import_(0, runner.to_device_bf16(r.prior_k), runner.to_device_bf16(r.prior_v))
+            kvs.append(kv)
+        x_dev = runner.to_device_bf16(x)
+        y_dev = torch.empty_like(x_dev)
+        call_shapes = [(t, p) for t, p in zip(lens, priors)]          # (T_i, P_i) of the one call
+        n_tokens, calls_per_step = wl.budget, 1
+
+        def step():
+            for kv, p in zip(kvs, priors):
+                kv.truncate(0, p)
+            stack.prefill_batch(0, kvs, lens, x_dev, y_dev)
+    else:
+        x = wl.prompt()
+        chunks = wl.chunks()
+        stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=1, max_pos=wl.n_tokens)
+        kv = stack.new_cache(wl.n_tokens)
+        x_dev = runner.to_device_bf16(x)
+        call_shapes = [(b - a, a) for a, b in chunks]
+        n_tokens, calls_per_step = wl.n_tokens, len(chunks) * wl.n_layers
+
+        def step():
+            kv.reset()
+            stack.prefill_prompt(x_dev, chunks, kv)
     del weights
-    kv = stack.new_cache(wl.n_tokens)
-    x_dev = runner.to_device_bf16(x)
 
-    def step():
-        kv.reset()
-        stack.prefill_prompt(x_dev, chunks, kv)
-
-    calls_per_step = len(chunks) * wl.n_layers
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -118,12 +146,17 @@ def main():
     gu_ms, gu_n = stack.ctx.profile_read()
     stack.ctx.profile_enable(None)
 
-    layer_tokens = wl.n_tokens * wl.n_layers
-    flops_step = wl.n_layers * sum(sh.linear_flops_per_token() * (b - a) + sh.attn_flops(b - a, a) for a, b in chunks)
+    layer_tokens = n_tokens * wl.n_layers
+    attn_flops_step = wl.n_layers * sum(sh.attn_flops(t, p) for t, p in call_shapes)
+    flops_step = wl.n_layers * sh.linear_flops_per_token() * n_tokens + attn_flops_step
+    # bytes of cached K and V that attention must read per step (prefix + the chunk itself), bf16
+    kv_bytes_step = wl.n_layers * sum((p + t) * 2 * sh.n_kv_heads * sh.head_dim * 2 for t, p in call_shapes)
     ms_per_step = dt / args.steps * 1e3
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    gu_flops = 2.0 * wl.budget * sh.hidden * 2 * sh.mlp_inter      # per launch: [2048, H] x [2I, H]^T
+    gu_rows = wl.budget if args.workload == 4 else max(t for t, _ in call_shapes)
+    gu_rows_avg = n_tokens * wl.n_layers / calls_per_step          # rows per launch, averaged (the last chunk may be short)
+    gu_flops = 2.0 * gu_rows_avg * sh.hidden * 2 * sh.mlp_inter    # per launch: [T, H] x [2I, H]^T
     gu_avg_ms = gu_ms / max(gu_n, 1)
     gu_tflops = gu_flops / (gu_avg_ms * 1e-3) / 1e12
     out = {
@@ -133,14 +166,18 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "layers": wl.n_layers, "prompt_tokens": wl.n_tokens, "token_budget": wl.budget,
-                   "calls_per_step": calls_per_step, "shape": "hidden 3584, 28 q / 4 kv heads, head_dim 128, mlp 18944"},
+        "config": {"workload": wl.name, "layers": wl.n_layers, "tokens_per_step": n_tokens, "token_budget": wl.budget,
+                   "calls_per_step": calls_per_step,
+                   "shape": f"hidden {sh.hidden}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, head_dim {sh.head_dim}, "
+                            f"mlp {sh.mlp_inter}"},
         "tflops": tflops,
         "mfma_frac_whole_path": tflops / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": {"kernel": "gemm_strip_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M=2048 K=3584 N=37888)",
+        "roofline": {"kernel": f"gemm_strip_kernel<EPI_SWIGLU> (gate/up + SwiGLU, M={gu_rows} K={sh.hidden} N={2 * sh.mlp_inter})",
                      "bound": "mfma", "achieved": gu_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": GATE_UP_TRAFFIC_BYTES,
-                     "traffic_unit": "bytes per launch (L2/fabric boundary, rocprofv3 --pmc)", "algorithmic_bytes": 363.9e6,
+                     "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": GATE_UP_TRAFFIC_BYTES if args.workload == 3 else None,
+                     "traffic_unit": "bytes per launch (L2/fabric boundary, rocprofv3 --pmc)",
+                     "algorithmic_bytes": 2.0 * (2 * sh.mlp_inter * sh.hidden + gu_rows_avg * (sh.hidden + sh.mlp_inter)),
                      "avg_ms": gu_avg_ms, "launches": gu_n},
     }
 
@@ -154,6 +191,9 @@ def main():
             bd[name] = ms / max(n, 1)
         stack.ctx.profile_enable(None)
         out["breakdown_avg_ms_per_call"] = bd
+        attn_s = bd["attention"] * 1e-3 * calls_per_step
+        out["attention"] = {"avg_ms": bd["attention"], "tflops": attn_flops_step / attn_s / 1e12,
+                            "kv_read_GBps": kv_bytes_step / attn_s / 1e9, "kv_read_frac_of_hbm_peak": kv_bytes_step / attn_s / 1e9 / HBM_PEAK_GBS}
 
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
