@@ -274,6 +274,28 @@ def test_scheduled_multi_request_prefill_matches_unchunked_oracle():
         check(f"scheduled req {rid} Y", _np(out[rid]), cur, tol=2 * TOL)
 
 
+def test_intra_request_pipeline_matches_unchunked_oracle():
+    """Algorithm 1 + the tracker + Algorithm 2 on one request with a stand-in encoder on a second stream: whatever
+    interleaving of encoding and prefill happens, the prefilled result equals the oracle's unchunked prefill."""
+    from paper_2509_24381_amd import pipeline
+    R = _runner()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 400, gains="uniform")
+    segs = [(False, 20), (True, 64), (True, 48), (False, 9), (True, 100), (False, 30)]
+    rows = synth.prompt_rows([("image" if mm else "text", n) for mm, n in segs], shape.hidden, 401)
+    stack = R.LayerStack(shape, [w], max_tokens=64, max_requests=1, max_pos=512)
+    enc = pipeline.StubEncoder(gflop_per_token=0.5, width=256)
+    y_ref, k_ref, v_ref = layer_forward(rows, LayerParams.from_arrays(shape, w))
+    for c in (1, 100, 10 ** 6):
+        res, kv, out = pipeline.run_intra_request_pipeline(stack, segs, _dev(rows), min_tokens=c, token_budget=64, encoder=enc)
+        assert sum(res.round_tokens) == rows.shape[0] and max(res.round_tokens) <= 64
+        k, v = kv.export(0)
+        check(f"pipeline C={c} Y", _np(out), y_ref)
+        check(f"pipeline C={c} K", _np(k), k_ref)
+        check(f"pipeline C={c} V", _np(v), v_ref)
+        print(f"[pipeline] C={c}: {res.n_encode_batches} encoder batches, {res.n_rounds} rounds, ttft {res.ttft_ms:.2f} ms", flush=True)
+
+
 # ------------------------------------------------------------------ production shapes
 def test_workload2_7b_2048_budget512():
     wl = synth.workload(2)
