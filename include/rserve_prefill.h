@@ -142,6 +142,29 @@ rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int laye
                            const void* x_dev, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* The same micro-batch through n_layers stacked layers in one call (layer l uses packed_layers[l] and the requests'
+ * layer-l caches; layer 0 reads x, every later layer reads the previous layer's output, the last one leaves y).  What a
+ * serving loop needs per scheduling round: section 3.3's BatchExecute for a whole model.  Every layer's capacity and
+ * size checks are made before the first launch, so a failing call changes nothing. */
+rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers,
+                                 rs_kv* const* kvs, const int* chunk_lens, int R,
+                                 const void* x_dev, void* y_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* First output token (what "time to first token", the paper's latency metric in section 4.1.4, waits for): final
+ * RMSNorm and vocabulary projection of n_rows hidden-state rows (the last prompt row of each request whose prefill has
+ * finished).
+ *   final_norm_gain  device bf16 [H]
+ *   w_lm             device bf16 [vocab, H], torch layout, used as is
+ *   x                device bf16 [n_rows, H]
+ *   logits           device fp32 [n_rows, vocab]:  logits[r, v] = sum_k rmsnorm(x[r])[k] * w_lm[v, k], fp32 accumulation,
+ *                    the normalised row kept in fp32
+ * workspace: rs_lm_head_workspace_bytes(ctx, n_rows) bytes, 256-byte aligned.  n_rows = 0 is a no-op. */
+size_t rs_lm_head_workspace_bytes(const rs_ctx* ctx, int n_rows);
+rs_status rs_lm_head(rs_ctx* ctx, const void* final_norm_gain_dev, const void* w_lm_dev, int vocab,
+                     const void* x_dev, int n_rows, void* logits_dev,
+                     void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement hook.  The steps of one rs_prefill_* call, in launch order: */
 typedef enum rs_step {
     RS_STEP_ROW_RMS = 0,       /* 1/rms of the input rows (first RMSNorm; gains are folded into the packed weights) */

@@ -7,7 +7,7 @@ obviously-correct statement of what the layer computes.
 """
 from .decoder_layer import (  # noqa: F401
     LayerParams, rmsnorm, rope_angles, rope, silu, causal_gqa_attention,
-    layer_forward, layer_forward_rows, ChunkedPrefill, prefill_batch, rel_fro,
+    layer_forward, layer_forward_rows, ChunkedPrefill, prefill_batch, first_token_logits, rel_fro,
 )
 from .brute_force import attention_loops  # noqa: F401
 from .scheduler import TrackedRequest, encoder_batches, schedule_round  # noqa: F401

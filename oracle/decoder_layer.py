@@ -297,6 +297,15 @@ def prefill_batch(states: List[ChunkedPrefill], chunks: List[np.ndarray]) -> np.
     return np.concatenate(outs, axis=0)
 
 
+def first_token_logits(x_rows: np.ndarray, gain: np.ndarray, w_lm: np.ndarray, eps: float) -> np.ndarray:
+    """Final RMSNorm and vocabulary projection of hidden-state rows: logits[r, v] = rmsnorm(x_r; gain) . w_lm[v].
+
+    The paper's latency metric is the time to the first token (section 4.1.4); this is the step that turns the last
+    prompt row's hidden state into that token's scores.  Same RMSNorm as inside the layers; w_lm in torch layout
+    [vocab, hidden]."""
+    return rmsnorm(x_rows, gain, eps) @ np.asarray(w_lm, dtype=F64).T
+
+
 def rel_fro(got: np.ndarray, want: np.ndarray) -> float:
     """Relative Frobenius error ||got - want||_F / ||want||_F (0 when both are empty/zero)."""
     got = np.asarray(got, dtype=F64)

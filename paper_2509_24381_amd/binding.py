@@ -21,7 +21,8 @@ STATUS = {0: "RS_OK", -1: "RS_EINVAL", -2: "RS_ECAPACITY", -3: "RS_EWORKSPACE", 
 EXPORTED_SYMBOLS = (
     "rs_ctx_create", "rs_ctx_destroy", "rs_weights_packed_bytes", "rs_weights_pack", "rs_kv_bytes", "rs_kv_alloc",
     "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
-    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_last_error", "rs_version",
+    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_lm_head_workspace_bytes",
+    "rs_lm_head", "rs_last_error", "rs_version",
     "rs_profile_enable", "rs_profile_read",
 )
 
@@ -98,6 +99,9 @@ def load_library():
         "rs_workspace_bytes": (sz, [vp, i, i]),
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
+        "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
+        "rs_lm_head_workspace_bytes": (sz, [vp, i]),
+        "rs_lm_head": (i, [vp, vp, vp, i, vp, i, vp, vp, sz, vp]),
         "rs_last_error": (C.c_char_p, []),
         "rs_version": (i, []),
         "rs_profile_enable": (i, [vp, i, i]),
@@ -296,6 +300,27 @@ class Context:
         _check(self.lib.rs_prefill_batch(self.handle, C.byref(packed.struct), layer, arr_kv, arr_len, r, _ptr(x), _ptr(y),
                                          _ptr(workspace), workspace.numel(), _stream_handle(stream)))
         return y
+
+    def prefill_model_batch(self, layers: Sequence[PackedWeights], kvs: Sequence[KVCache], chunk_lens: Sequence[int],
+                            x, y, workspace, stream=None):
+        """One micro-batch through all stacked layers in one call; x, y: bf16 [sum chunk_lens, H]."""
+        r = len(kvs)
+        arr_w = (_Weights * max(len(layers), 1))(*[l.struct for l in layers])
+        arr_kv = (C.c_void_p * max(r, 1))(*[k.handle.value for k in kvs])
+        arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
+        _check(self.lib.rs_prefill_model_batch(self.handle, arr_w, len(layers), arr_kv, arr_len, r, _ptr(x), _ptr(y),
+                                               _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+        return y
+
+    def lm_head(self, final_norm_gain, w_lm, x_rows, stream=None):
+        """fp32 logits [n_rows, vocab] of bf16 hidden-state rows x_rows [n_rows, H]: final RMSNorm + vocabulary projection."""
+        import torch
+        n, vocab = int(x_rows.shape[0]), int(w_lm.shape[0])
+        logits = torch.empty((n, vocab), dtype=torch.float32, device=x_rows.device)
+        ws = torch.empty(max(int(self.lib.rs_lm_head_workspace_bytes(self.handle, n)), 256), dtype=torch.uint8, device=x_rows.device)
+        _check(self.lib.rs_lm_head(self.handle, _ptr(final_norm_gain), _ptr(w_lm), vocab, _ptr(x_rows), n, _ptr(logits),
+                                   _ptr(ws), ws.numel(), _stream_handle(stream)))
+        return logits
 
 
 class Scheduler:

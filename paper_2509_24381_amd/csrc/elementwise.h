@@ -53,6 +53,80 @@ __global__ __launch_bounds__(256) void rowss_finalize_kernel(const float* __rest
     if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)H + eps);
 }
 
+// ---------------------------------------------------------------- first-token head: final RMSNorm + vocabulary projection
+// h[r][k] = x[r][k] * g[k] * rsqrt(mean(x[r]^2) + eps), kept in fp32.  One wavefront per row.
+__global__ __launch_bounds__(256) void final_norm_kernel(const bf16* __restrict__ x, const bf16* __restrict__ gain,
+                                                         float* __restrict__ h, int rows, int H, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const bf16* xr = x + (size_t)row * H;
+    float ss = 0.0f;
+    for (int c = lane; c < H / 8; c += WAVE) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += bf16_to_f32(v[e]) * bf16_to_f32(v[e]);
+    }
+    ss = wave_sum(ss);
+    const float inv = rsqrtf(ss / (float)H + eps);
+    for (int c = lane; c < H / 8; c += WAVE) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c * 8);
+        const bf16x8 g = *reinterpret_cast<const bf16x8*>(gain + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[(size_t)row * H + c * 8 + e] = bf16_to_f32(v[e]) * inv * bf16_to_f32(g[e]);
+    }
+}
+
+// logits[r][v] = sum_k h[r][k] * w[v][k] for R <= LM_ROWS rows at a time.  HBM-bound on the vocabulary matrix (read once):
+// the normalised rows sit in LDS (fp32); each wavefront walks the vocabulary four rows at a time, its 64 lanes covering
+// K in contiguous 16-byte chunks (1 KB per load instruction and row), so that one LDS read of the activations serves
+// four weight rows; lanes are reduced at the end of the group.
+constexpr int LM_ROWS = 4;
+constexpr int LM_VGROUP = 4;
+__global__ __launch_bounds__(256) void lm_head_kernel(const bf16* __restrict__ w, const float* __restrict__ h,
+                                                      float* __restrict__ logits, int R, int vocab, int H) {
+    extern __shared__ __attribute__((aligned(16))) float h_lds[];  // [R][H]
+    for (int i = threadIdx.x; i < R * H / 4; i += blockDim.x)
+        reinterpret_cast<f32x4*>(h_lds)[i] = reinterpret_cast<const f32x4*>(h)[i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int v0 = (blockIdx.x * 4 + wave) * LM_VGROUP; v0 < vocab; v0 += gridDim.x * 4 * LM_VGROUP) {
+        const bf16* wr[LM_VGROUP];
+#pragma unroll
+        for (int j = 0; j < LM_VGROUP; ++j) wr[j] = w + (size_t)min(v0 + j, vocab - 1) * H;  // rows past the end repeat the last one
+        float acc[LM_VGROUP][LM_ROWS];
+#pragma unroll
+        for (int j = 0; j < LM_VGROUP; ++j)
+#pragma unroll
+            for (int r = 0; r < LM_ROWS; ++r) acc[j][r] = 0.0f;
+        for (int c = lane; c < H / 8; c += WAVE) {
+            bf16x8 wv[LM_VGROUP];
+#pragma unroll
+            for (int j = 0; j < LM_VGROUP; ++j) wv[j] = *reinterpret_cast<const bf16x8*>(wr[j] + c * 8);
+#pragma unroll
+            for (int r = 0; r < LM_ROWS; ++r)
+                if (r < R) {
+                    const f32x4 h0 = *reinterpret_cast<const f32x4*>(h_lds + (size_t)r * H + c * 8);
+                    const f32x4 h1 = *reinterpret_cast<const f32x4*>(h_lds + (size_t)r * H + c * 8 + 4);
+#pragma unroll
+                    for (int j = 0; j < LM_VGROUP; ++j)
+                        acc[j][r] += bf16_to_f32(wv[j][0]) * h0[0] + bf16_to_f32(wv[j][1]) * h0[1] + bf16_to_f32(wv[j][2]) * h0[2] +
+                                     bf16_to_f32(wv[j][3]) * h0[3] + bf16_to_f32(wv[j][4]) * h1[0] + bf16_to_f32(wv[j][5]) * h1[1] +
+                                     bf16_to_f32(wv[j][6]) * h1[2] + bf16_to_f32(wv[j][7]) * h1[3];
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < LM_VGROUP; ++j)
+#pragma unroll
+            for (int r = 0; r < LM_ROWS; ++r)
+                if (r < R) {
+                    const float t = wave_sum(acc[j][r]);
+                    if (lane == 0 && v0 + j < vocab) logits[(size_t)r * vocab + v0 + j] = t;
+                }
+    }
+}
+
 // ---------------------------------------------------------------- K / V append
 struct KVBlockItem {
     int req;

@@ -257,8 +257,9 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     return RS_OK;
 }
 
-rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
-                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream) {
+// Every check of one layer's call; changes nothing.  *total_out receives the number of rows.
+rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
+                        const void* x, void* y, void* ws, size_t ws_bytes, int* total_out) {
     if (!ctx) return fail(RS_EINVAL, "ctx is null");
     if (!w) return fail(RS_EINVAL, "weights are null");
     const rs_layer_cfg& f = ctx->cfg;
@@ -290,6 +291,7 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
             return fail(RS_ECAPACITY, "request %d: %ld tokens exceed cache capacity %d", i, after, kvs[i]->cap);
         if (after > f.max_pos) return fail(RS_ECAPACITY, "request %d: %ld tokens exceed max_pos %d", i, after, f.max_pos);
     }
+    *total_out = (int)total;
     if (total == 0) return RS_OK;
     const int T = (int)total;
     if (!x || !y) return fail(RS_EINVAL, "x / y is null");
@@ -299,6 +301,14 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     const WorkspaceLayout L = ws_layout(ctx, T, R);
     if (ws_bytes < L.total) return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, L.total);
     if (!ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
+    return RS_OK;
+}
+
+// Enqueues one layer's call (arguments already checked by prefill_check) and advances the cache lengths.
+rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R, int T,
+                          const void* x, void* y, void* ws, void* stream) {
+    const rs_layer_cfg& f = ctx->cfg;
+    const WorkspaceLayout L = ws_layout(ctx, T, R);
 
     // ---- host descriptors
     std::vector<ReqDesc> reqs;
@@ -417,6 +427,14 @@ rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv*
     return RS_OK;
 }
 
+rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
+                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream) {
+    int T = 0;
+    const rs_status s = prefill_check(ctx, w, layer, kvs, lens, R, x, y, ws, ws_bytes, &T);
+    if (s != RS_OK || T == 0) return s;
+    return prefill_enqueue(ctx, w, layer, kvs, lens, R, T, x, y, ws, stream);
+}
+
 }  // namespace
 
 // =============================================================================================== C ABI
@@ -495,6 +513,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)lm_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LM_ROWS * f.hidden * 4);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
     // (the pipelined attention kernel keeps its LDS in static arrays; these references make the launch stubs exist)
@@ -721,6 +740,57 @@ rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int laye
 rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* const* kvs, const int* chunk_lens, int R,
                            const void* x, void* y, void* workspace, size_t workspace_bytes, void* stream) {
     return prefill_impl(ctx, packed, layer, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, stream);
+}
+
+rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs,
+                                 const int* chunk_lens, int R, const void* x, void* y, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!packed_layers) return fail(RS_EINVAL, "packed_layers is null");
+    if (n_layers <= 0) return fail(RS_EINVAL, "n_layers = %d must be positive", n_layers);
+    int T = 0;
+    for (int l = 0; l < n_layers; ++l) {  // all checks first: a failing call leaves every cache untouched
+        const rs_status s = prefill_check(ctx, &packed_layers[l], l, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, &T);
+        if (s != RS_OK) return s;
+    }
+    if (T == 0) return RS_OK;
+    for (int l = 0; l < n_layers; ++l) {  // layer 0 reads x; later layers work on y in place
+        const rs_status s = prefill_enqueue(ctx, &packed_layers[l], l, kvs, chunk_lens, R, T, l == 0 ? x : y, y, workspace, stream);
+        if (s != RS_OK) return s;
+    }
+    return RS_OK;
+}
+
+size_t rs_lm_head_workspace_bytes(const rs_ctx* c, int n_rows) {
+    if (!c || n_rows <= 0) return 0;
+    return align_up((size_t)n_rows * c->cfg.hidden * 4, 256);
+}
+
+rs_status rs_lm_head(rs_ctx* c, const void* final_norm_gain, const void* w_lm, int vocab, const void* x, int n_rows, void* logits,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (!c) return fail(RS_EINVAL, "ctx is null");
+    if (n_rows < 0) return fail(RS_EINVAL, "n_rows = %d is negative", n_rows);
+    if (vocab <= 0) return fail(RS_EINVAL, "vocab = %d must be positive", vocab);
+    if (n_rows == 0) return RS_OK;
+    if (!final_norm_gain || !w_lm || !x || !logits || !workspace) return fail(RS_EINVAL, "null argument");
+    if (!aligned(final_norm_gain, 16) || !aligned(w_lm, 16) || !aligned(x, 16) || !aligned(logits, 4) || !aligned(workspace, 256))
+        return fail(RS_EINVAL, "misaligned argument");
+    if (workspace_bytes < rs_lm_head_workspace_bytes(c, n_rows))
+        return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", workspace_bytes, rs_lm_head_workspace_bytes(c, n_rows));
+    if (!c->has_device) return fail(RS_EHIP, "no HIP device");
+    const int H = c->cfg.hidden;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    float* h = reinterpret_cast<float*>(workspace);
+    hipLaunchKernelGGL(final_norm_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, st, (const bf16*)x, (const bf16*)final_norm_gain, h,
+                       n_rows, H, c->cfg.rms_eps);
+    RS_HIP(hipGetLastError());
+    const int blocks = std::min(4 * c->n_cu, (vocab + 4 * LM_VGROUP - 1) / (4 * LM_VGROUP));
+    for (int r0 = 0; r0 < n_rows; r0 += LM_ROWS) {  // the vocabulary matrix is streamed once per group of LM_ROWS rows
+        const int R = std::min(LM_ROWS, n_rows - r0);
+        hipLaunchKernelGGL(lm_head_kernel, dim3(blocks), dim3(256), (size_t)R * H * 4, st, (const bf16*)w_lm, (const float*)(h + (size_t)r0 * H),
+                           reinterpret_cast<float*>(logits) + (size_t)r0 * vocab, R, vocab, H);
+        RS_HIP(hipGetLastError());
+    }
+    return RS_OK;
 }
 
 }  // extern "C"

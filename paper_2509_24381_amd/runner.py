@@ -97,7 +97,7 @@ def run_scheduled_round(stack: LayerStack, entries, embeddings, kvs, outputs) ->
     entries: what Scheduler.next_round() returned; embeddings / kvs / outputs: dicts keyed by request id holding the
     request's bf16 [p, H] embedding tensor (the tracker's cache), its KVCache and the [p, H] tensor that receives the last
     layer's output.  Gathers the scheduled rows into the packed micro-batch input, runs every layer with
-    rs_prefill_batch, scatters the result.  Returns the number of tokens run.
+    rs_prefill_model_batch, scatters the result.  Returns the number of tokens run.
     """
     import torch
     live = [(rid, first, n) for rid, first, n, _ in entries if n > 0]
@@ -106,10 +106,7 @@ def run_scheduled_round(stack: LayerStack, entries, embeddings, kvs, outputs) ->
     x = torch.cat([embeddings[rid][first: first + n] for rid, first, n in live], dim=0)
     lens = [n for _, _, n in live]
     batch_kvs = [kvs[rid] for rid, _, _ in live]
-    y = torch.empty_like(x)
-    for l in range(stack.n_layers):
-        stack.prefill_batch(l, batch_kvs, lens, x, y)
-        x, y = y, x
+    stack.ctx.prefill_model_batch(stack.layers, batch_kvs, lens, x, x, stack.ws)   # all layers, in place
     off = 0
     for rid, first, n in live:
         outputs[rid][first: first + n] = x[off: off + n]

@@ -296,6 +296,59 @@ def test_intra_request_pipeline_matches_unchunked_oracle():
         print(f"[pipeline] C={c}: {res.n_encode_batches} encoder batches, {res.n_rounds} rounds, ttft {res.ttft_ms:.2f} ms", flush=True)
 
 
+def test_model_batch_equals_layer_by_layer_calls_bit_for_bit():
+    """rs_prefill_model_batch is the per-layer calls in a loop: outputs and caches must be identical bits."""
+    R = _runner()
+    shape = synth.TINY
+    ws = [synth.layer_weights(shape, 500 + l, gains="uniform", qkv_bias=True) for l in range(3)]
+    stack = R.LayerStack(shape, ws, max_tokens=200, max_requests=3, max_pos=512, qkv_bias=True)
+    rows = [synth.prompt_rows([("image", n // 2), ("text", n - n // 2)], shape.hidden, 510 + i) for i, n in enumerate((70, 1, 129))]
+    x = _dev(np.concatenate(rows))
+    lens = [r.shape[0] for r in rows]
+    kv_a = [stack.new_cache(256) for _ in rows]
+    kv_b = [stack.new_cache(256) for _ in rows]
+    y_a = torch.empty_like(x)
+    stack.ctx.prefill_model_batch(stack.layers, kv_a, lens, x, y_a, stack.ws)
+    cur = x
+    for l in range(3):
+        nxt = torch.empty_like(x)
+        stack.prefill_batch(l, kv_b, lens, cur, nxt)
+        cur = nxt
+    torch.cuda.synchronize()
+    assert torch.equal(y_a, cur)
+    for a, b in zip(kv_a, kv_b):
+        for l in range(3):
+            assert a.length(l) == b.length(l)
+            (ka, va), (kb, vb) = a.export(l), b.export(l)
+            assert torch.equal(ka, kb) and torch.equal(va, vb)
+    # a call that cannot fit (layer 2 of request 0 is made one token short) changes nothing anywhere
+    from paper_2509_24381_amd.binding import RsError
+    small = stack.new_cache(64)
+    with pytest.raises(RsError) as e:
+        stack.ctx.prefill_model_batch(stack.layers, [small], [65], x[:65], y_a[:65], stack.ws)
+    assert e.value.status_name == "RS_ECAPACITY" and [small.length(l) for l in range(3)] == [0, 0, 0]
+
+
+@pytest.mark.parametrize("hidden, vocab, n_rows", [(256, 1000, 1), (256, 1003, 6), (3584, 32000, 3)])
+def test_first_token_logits(hidden, vocab, n_rows):
+    """Final RMSNorm + vocabulary projection against the oracle (fp32 accumulation of bf16 weights: well inside 1e-2)."""
+    from oracle import first_token_logits
+    R = _runner()
+    shape = synth.LayerShape("lm", hidden, 4, 2, 64, 1024)
+    stack = R.LayerStack(shape, [synth.layer_weights(shape, 600)], max_tokens=32, max_requests=1, max_pos=64)
+    rng = np.random.default_rng(601)
+    g = synth.bf16_round(rng.uniform(0.5, 1.5, hidden).astype(np.float32))
+    w = synth.bf16_round((rng.standard_normal((vocab, hidden)) * 0.02).astype(np.float32))
+    x = synth.bf16_round(rng.standard_normal((n_rows, hidden)).astype(np.float32) * np.float32(3.0))
+    logits = stack.ctx.lm_head(_dev(g), _dev(w), _dev(x))
+    torch.cuda.synchronize()
+    want = first_token_logits(x, g, w, shape.rms_eps)
+    got = logits.cpu().numpy()
+    check(f"logits H={hidden} V={vocab} R={n_rows}", got, want, tol=1e-3)
+    assert np.array_equal(got.argmax(axis=1), want.argmax(axis=1)) or np.all(
+        np.abs(np.sort(want, axis=1)[:, -1] - np.sort(want, axis=1)[:, -2]) < 1e-3 * np.abs(want).max())
+
+
 # ------------------------------------------------------------------ production shapes
 def test_workload2_7b_2048_budget512():
     wl = synth.workload(2)

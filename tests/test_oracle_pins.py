@@ -395,3 +395,25 @@ def test_chunk_attention_matches_scalar_loops_with_prefix():
     q = rope(q, pos, p.rope_theta); kn = rope(kn, pos, p.rope_theta)
     o, _ = attention_loops(q.tolist(), np.concatenate([pk, kn]).tolist(), np.concatenate([pv, vn]).tolist(), n_prior=prior)
     np.testing.assert_allclose(y - x, np.array(o).reshape(t, 16), atol=1e-12)
+
+
+def test_first_token_logits_closed_form_on_one_hot_rows():
+    """x = c e_k: mean(x^2) = c^2/H, so rmsnorm(x) = sign(c) sqrt(H) / sqrt(1 + eps H / c^2) g_k e_k and the logits are
+    that factor times column k of w_lm; a constant row with unit gain gives the row sums of w_lm (eps -> 0)."""
+    import oracle
+    rng = np.random.default_rng(77)
+    h, vocab, eps = 48, 19, 1e-6
+    g = rng.uniform(0.5, 1.5, h)
+    w = rng.standard_normal((vocab, h))
+    for k, c in ((0, 2.0), (17, -0.3), (47, 1e-2)):
+        x = np.zeros((1, h))
+        x[0, k] = c
+        want = np.sign(c) * np.sqrt(h) / np.sqrt(1.0 + eps * h / c ** 2) * g[k] * w[:, k]
+        np.testing.assert_allclose(oracle.first_token_logits(x, g, w, eps)[0], want, rtol=1e-12, atol=1e-12)
+    got = oracle.first_token_logits(np.full((2, h), 3.0), np.ones(h), w, 0.0)
+    np.testing.assert_allclose(got, np.tile(w.sum(axis=1), (2, 1)), rtol=1e-12)
+    # rows are independent, and the result is linear in w_lm
+    x = rng.standard_normal((3, h))
+    a = oracle.first_token_logits(x, g, w, eps)
+    np.testing.assert_allclose(oracle.first_token_logits(x[1:2], g, w, eps), a[1:2], rtol=1e-13)
+    np.testing.assert_allclose(oracle.first_token_logits(x, g, 2.0 * w, eps), 2.0 * a, rtol=1e-13)
