@@ -142,6 +142,21 @@ rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int laye
                            const void* x_dev, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* Three-axis rotary positions (the M-RoPE of the model family the paper serves, section 4.1.1; not part of the paper's
+ * own text).  The d/2 rotary pairs of a head are split into three consecutive sections; pair j is turned by the row's
+ * temporal, height or width position according to the section it falls in.  Sections are counts of pairs, multiples of
+ * 4, summing to head_dim / 2; the default after rs_ctx_create is (head_dim / 2, 0, 0), i.e. 1-D RoPE.  Applies to every
+ * later call on the context. */
+rs_status rs_ctx_set_mrope_sections(rs_ctx* ctx, int temporal, int height, int width);
+
+/* rs_prefill_batch with explicit rotary positions: positions is a HOST array [sum chunk_lens][3] of (temporal, height,
+ * width) positions in packed row order, each in [0, max_pos) (RS_ECAPACITY otherwise).  Only the rotation uses them:
+ * cache slots and the causal order stay P..P+T-1.  With all three equal to P+i this is rs_prefill_batch. */
+rs_status rs_prefill_batch_mrope(rs_ctx* ctx, const rs_layer_weights* packed, int layer,
+                                 rs_kv* const* kvs, const int* chunk_lens, int R, const int* positions,
+                                 const void* x_dev, void* y_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* The same micro-batch through n_layers stacked layers in one call (layer l uses packed_layers[l] and the requests'
  * layer-l caches; layer 0 reads x, every later layer reads the previous layer's output, the last one leaves y).  What a
  * serving loop needs per scheduling round: section 3.3's BatchExecute for a whole model.  Every layer's capacity and

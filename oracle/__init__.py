@@ -6,7 +6,7 @@ the smoke check and the benchmark's CPU-baseline leg have an independent,
 obviously-correct statement of what the layer computes.
 """
 from .decoder_layer import (  # noqa: F401
-    LayerParams, rmsnorm, rope_angles, rope, silu, causal_gqa_attention,
+    LayerParams, rmsnorm, rope_angles, mrope_angles, rope, silu, causal_gqa_attention,
     layer_forward, layer_forward_rows, ChunkedPrefill, prefill_batch, first_token_logits, rel_fro,
 )
 from .brute_force import attention_loops  # noqa: F401

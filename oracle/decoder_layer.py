@@ -96,12 +96,28 @@ def rope_angles(positions: np.ndarray, head_dim: int, theta: float) -> np.ndarra
     return np.asarray(positions, dtype=F64)[:, None] * inv_freq[None, :]
 
 
-def rope(v: np.ndarray, positions: np.ndarray, theta: float) -> np.ndarray:
-    """Rotate-half RoPE on v[n, head, d]: pairs (j, j + d/2) are rotated by phi[n, j]."""
+def mrope_angles(positions3: np.ndarray, head_dim: int, theta: float, sections: Sequence[int]) -> np.ndarray:
+    """Three-axis rotary angles (the M-RoPE of the model family the paper serves; not in the paper's own text):
+    positions3[n] = (temporal, height, width); the d/2 pairs are split into consecutive sections of sections[0],
+    sections[1], sections[2] pairs, and pair j in section a turns by positions3[n, a] * theta^(-2j/d)."""
+    assert sum(sections) == head_dim // 2
+    positions3 = np.asarray(positions3, dtype=F64)
+    phi = np.empty((positions3.shape[0], head_dim // 2), dtype=F64)
+    j0 = 0
+    for axis, count in enumerate(sections):
+        for j in range(j0, j0 + count):
+            phi[:, j] = positions3[:, axis] * theta ** (-2.0 * j / head_dim)
+        j0 += count
+    return phi
+
+
+def rope(v: np.ndarray, positions: np.ndarray, theta: float, sections: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Rotate-half RoPE on v[n, head, d]: pairs (j, j + d/2) are rotated by phi[n, j].  positions is [n] (1-D RoPE)
+    or, with `sections`, [n, 3] (three-axis RoPE, see mrope_angles)."""
     v = np.asarray(v, dtype=F64)
     d = v.shape[-1]
     half = d // 2
-    phi = rope_angles(positions, d, theta)
+    phi = rope_angles(positions, d, theta) if sections is None else mrope_angles(positions, d, theta, sections)
     c = np.cos(phi)[:, None, :]
     s = np.sin(phi)[:, None, :]
     lo, hi = v[..., :half], v[..., half:]
@@ -178,18 +194,20 @@ def _mlp_residual(r: np.ndarray, p: LayerParams) -> np.ndarray:
     return r + a @ p.wd.T
 
 
-def layer_forward(x: np.ndarray, p: LayerParams) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def layer_forward(x: np.ndarray, p: LayerParams, positions3: Optional[np.ndarray] = None,
+                  sections: Optional[Sequence[int]] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Unchunked prefill of one request through one layer.
 
-    x[N, hidden] -> (Y[N, hidden], K~[N, Hkv, d] post-RoPE, V[N, Hkv, d]); token n sits at position n.
+    x[N, hidden] -> (Y[N, hidden], K~[N, Hkv, d] post-RoPE, V[N, Hkv, d]); token n sits at position n, or - when
+    positions3[N, 3] and sections are given - is rotated by its three-axis position (causal order stays n).
     """
     x = np.asarray(x, dtype=F64)
     n = x.shape[0]
-    pos = np.arange(n)
+    pos = np.arange(n) if positions3 is None else positions3
     h = rmsnorm(x, p.g1, p.rms_eps)
     q, k, v = _project_qkv(h, p)
-    q = rope(q, pos, p.rope_theta)
-    k = rope(k, pos, p.rope_theta)
+    q = rope(q, pos, p.rope_theta, sections if positions3 is not None else None)
+    k = rope(k, pos, p.rope_theta, sections if positions3 is not None else None)
     o = causal_gqa_attention(q, k, v)
     r = x + o.reshape(n, p.n_q_heads * p.head_dim) @ p.wo.T
     y = _mlp_residual(r, p)

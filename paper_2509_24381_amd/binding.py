@@ -21,7 +21,8 @@ STATUS = {0: "RS_OK", -1: "RS_EINVAL", -2: "RS_ECAPACITY", -3: "RS_EWORKSPACE", 
 EXPORTED_SYMBOLS = (
     "rs_ctx_create", "rs_ctx_destroy", "rs_weights_packed_bytes", "rs_weights_pack", "rs_kv_bytes", "rs_kv_alloc",
     "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
-    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_lm_head_workspace_bytes",
+    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
+    "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
     "rs_profile_enable", "rs_profile_read",
 )
@@ -100,6 +101,8 @@ def load_library():
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
+        "rs_ctx_set_mrope_sections": (i, [vp, i, i, i]),
+        "rs_prefill_batch_mrope": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, C.POINTER(i), vp, vp, vp, sz, vp]),
         "rs_lm_head_workspace_bytes": (sz, [vp, i]),
         "rs_lm_head": (i, [vp, vp, vp, i, vp, i, vp, vp, sz, vp]),
         "rs_last_error": (C.c_char_p, []),
@@ -299,6 +302,22 @@ class Context:
         arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
         _check(self.lib.rs_prefill_batch(self.handle, C.byref(packed.struct), layer, arr_kv, arr_len, r, _ptr(x), _ptr(y),
                                          _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+        return y
+
+    def set_mrope_sections(self, temporal: int, height: int, width: int):
+        _check(self.lib.rs_ctx_set_mrope_sections(self.handle, temporal, height, width))
+
+    def prefill_batch_mrope(self, packed: PackedWeights, layer: int, kvs: Sequence[KVCache], chunk_lens: Sequence[int],
+                            positions, x, y, workspace, stream=None):
+        """rs_prefill_batch with explicit (temporal, height, width) rotary positions: positions is an int array-like
+        [sum chunk_lens, 3] on the host."""
+        r = len(kvs)
+        flat = [int(v) for row in positions for v in row]
+        arr_pos = (C.c_int * max(len(flat), 1))(*flat)
+        arr_kv = (C.c_void_p * max(r, 1))(*[k.handle.value for k in kvs])
+        arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
+        _check(self.lib.rs_prefill_batch_mrope(self.handle, C.byref(packed.struct), layer, arr_kv, arr_len, r, arr_pos, _ptr(x),
+                                               _ptr(y), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
         return y
 
     def prefill_model_batch(self, layers: Sequence[PackedWeights], kvs: Sequence[KVCache], chunk_lens: Sequence[int],

@@ -47,7 +47,8 @@ struct GemmArgs {
     float* rowss;       // EPI_RESIDUAL: [M][N/32] sum of squares of each stored run of 32 features, or null
     float* partial;     // [splits, M, N]
     const float* row_scale;  // [M] 1/rms of the row (EPI_QKV_ROPE, EPI_SWIGLU)
-    const int* row_pos;      // [M] absolute position of the row (EPI_QKV_ROPE)
+    const int* row_pos;      // [M][3] rotary position of the row on the (temporal, height, width) axes (EPI_QKV_ROPE)
+    int mrope_b0, mrope_b1;  // rotary pair j uses axis 0 if j < b0, axis 1 if j < b1, else axis 2 (1-D RoPE: b0 = b1 = d/2)
     const float2* rope_cs;   // [max_pos][head_dim/2] (cos, sin)
     int rope_cols;           // columns [0, rope_cols) are q and k heads (a multiple of head_dim)
     int head_dim;            // 64 or 128
@@ -136,12 +137,13 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
         } else if constexpr (EPI == EPI_QKV_ROPE) {
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t r_sc = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_scale, 0, a.M * 4, RSRC_FLAGS);
-            const __amdgpu_buffer_rsrc_t r_pos = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_pos, 0, a.M * 4, RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t r_pos = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_pos, 0, a.M * 12, RSRC_FLAGS);
             const float sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r_sc, m * 4, 0, 0));
-            const int pos = (int)__builtin_amdgcn_raw_buffer_load_b32(r_pos, m * 4, 0, 0);  // 0 for a row past M
+            int pos3[3];  // 0 for a row past M
+#pragma unroll
+            for (int ax = 0; ax < 3; ++ax) pos3[ax] = (int)__builtin_amdgcn_raw_buffer_load_b32(r_pos, m * 12 + ax * 4, 0, 0);
             const int hd2 = a.head_dim >> 1;
             const int uph_shift = (a.head_dim == 128) ? 2 : 1;  // a head is 4 or 2 units
-            const float2* csr = a.rope_cs + (size_t)pos * hd2;
             const uint32_t orow = (uint32_t)m * (uint32_t)a.ldo * 2u;
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
@@ -150,10 +152,14 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     // rows 0..15 of the unit are features f..f+15 of the head's first half, rows 16..31 their partners
                     const int uh = gu & ((1 << uph_shift) - 1);
                     const int fl = (gu >> uph_shift) * a.head_dim + uh * 16 + 4 * half;  // column of this lane's first "low" run
-                    const float2* cs = csr + uh * 16 + 4 * half;
                     bf16x4 olq[2], ohq[2];
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
+                        // rotary pair index of this lane's run, and the axis whose position turns it (section bounds are
+                        // multiples of 4, so a run of 4 never straddles one)
+                        const int j0 = uh * 16 + 8 * q + 4 * half;
+                        const int pos = j0 < a.mrope_b0 ? pos3[0] : (j0 < a.mrope_b1 ? pos3[1] : pos3[2]);
+                        const float2* cs = a.rope_cs + (size_t)pos * hd2 + j0;
                         float bl[4] = {0.0f, 0.0f, 0.0f, 0.0f}, bh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                         if (a.bias != nullptr) {
                             const bf16x4 b0 = *reinterpret_cast<const bf16x4*>(a.bias + fl + 8 * q);
@@ -169,7 +175,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                         for (int e = 0; e < 4; ++e) {
                             const float lo = acc[i][j][4 * q + e] * sc + bl[e];
                             const float hi = acc[i][j][8 + 4 * q + e] * sc + bh[e];
-                            const float2 c = cs[8 * q + e];
+                            const float2 c = cs[e];
                             ol[e] = f32_to_bf16(lo * c.x - hi * c.y);
                             oh[e] = f32_to_bf16(hi * c.x + lo * c.y);
                         }

@@ -69,6 +69,7 @@ struct rs_ctx {
     size_t slot_bytes = 0;
     int next_slot = 0;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
+    int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
     int attn_variant = 1;     // RS_ATTN environment variable: 1 software-pipelined attention kernel, 0 the plain one
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
@@ -103,7 +104,7 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     d.reqs = align_up(sizeof(ReqDesc) * std::max(max_requests, 1), 256);
     d.items = align_up(sizeof(AttnItem) * n_items, 256);
     d.vblocks = align_up(sizeof(KVBlockItem) * n_vb, 256);
-    d.rowpos = align_up(sizeof(int) * (size_t)std::max(max_tokens, 1), 256);
+    d.rowpos = align_up(3 * sizeof(int) * (size_t)std::max(max_tokens, 1), 256);  // (temporal, height, width) per row
     d.total = d.reqs + d.items + d.vblocks + d.rowpos;
     return d;
 }
@@ -259,7 +260,7 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
 
 // Every check of one layer's call; changes nothing.  *total_out receives the number of rows.
 rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
-                        const void* x, void* y, void* ws, size_t ws_bytes, int* total_out) {
+                        const void* x, void* y, void* ws, size_t ws_bytes, int* total_out, const int* positions3 = nullptr) {
     if (!ctx) return fail(RS_EINVAL, "ctx is null");
     if (!w) return fail(RS_EINVAL, "weights are null");
     const rs_layer_cfg& f = ctx->cfg;
@@ -294,6 +295,10 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
     *total_out = (int)total;
     if (total == 0) return RS_OK;
     const int T = (int)total;
+    if (positions3)
+        for (long i = 0; i < 3 * total; ++i)
+            if (positions3[i] < 0 || positions3[i] >= f.max_pos)
+                return fail(RS_ECAPACITY, "rotary position %d of row %ld is outside [0, max_pos = %d)", positions3[i], i / 3, f.max_pos);
     if (!x || !y) return fail(RS_EINVAL, "x / y is null");
     if (!aligned(x, 16) || !aligned(y, 16)) return fail(RS_EINVAL, "x / y must be 16-byte aligned");
     if (!ws) return fail(RS_EINVAL, "workspace is null");
@@ -306,7 +311,7 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
 
 // Enqueues one layer's call (arguments already checked by prefill_check) and advances the cache lengths.
 rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R, int T,
-                          const void* x, void* y, void* ws, void* stream) {
+                          const void* x, void* y, void* ws, void* stream, const int* positions3 = nullptr) {
     const rs_layer_cfg& f = ctx->cfg;
     const WorkspaceLayout L = ws_layout(ctx, T, R);
 
@@ -315,7 +320,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     std::vector<AttnItem> items;
     std::vector<KVBlockItem> vbs;
     std::vector<int> rowpos;
-    rowpos.reserve(T);
+    rowpos.reserve(3 * (size_t)T);
     const int g = ctx->group;
     int row0 = 0;
     for (int i = 0; i < R; ++i) {
@@ -336,7 +341,8 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
             for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb});
         }
         for (int b = P / 64; b <= (P + Ti - 1) / 64; ++b) vbs.push_back(KVBlockItem{ri, b});
-        for (int t = 0; t < Ti; ++t) rowpos.push_back(P + t);
+        for (int t = 0; t < Ti; ++t)
+            for (int ax = 0; ax < 3; ++ax) rowpos.push_back(positions3 ? positions3[3 * (size_t)(row0 + t) + ax] : P + t);
         row0 += Ti;
     }
     // heaviest work first: the tail of the launch is then made of short items
@@ -394,6 +400,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         a.bias = f.qkv_bias ? (const bf16*)w->b_qkv : nullptr;
         a.row_scale = inv_rms1; a.row_pos = d_rowpos; a.rope_cs = (const float2*)ctx->rope_dev;
         a.rope_cols = ctx->q_dim + ctx->kv_dim; a.head_dim = f.head_dim;
+        a.mrope_b0 = ctx->mrope_b0; a.mrope_b1 = ctx->mrope_b1;
         a.M = T; a.N = ctx->qkv_dim; a.K = H;
         if ((s = launch_gemm<EPI_QKV_ROPE>(ctx, a, 1, st)) != RS_OK) return s;
     }
@@ -428,11 +435,11 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
 }
 
 rs_status prefill_impl(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
-                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream) {
+                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream, const int* positions3 = nullptr) {
     int T = 0;
-    const rs_status s = prefill_check(ctx, w, layer, kvs, lens, R, x, y, ws, ws_bytes, &T);
+    const rs_status s = prefill_check(ctx, w, layer, kvs, lens, R, x, y, ws, ws_bytes, &T, positions3);
     if (s != RS_OK || T == 0) return s;
-    return prefill_enqueue(ctx, w, layer, kvs, lens, R, T, x, y, ws, stream);
+    return prefill_enqueue(ctx, w, layer, kvs, lens, R, T, x, y, ws, stream, positions3);
 }
 
 }  // namespace
@@ -467,6 +474,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     rs_ctx* c = new rs_ctx();
     c->cfg = f;
     c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
+    c->mrope_b0 = c->mrope_b1 = f.head_dim / 2;  // 1-D RoPE: every pair turns with the first axis
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
     if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
@@ -740,6 +748,24 @@ rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int laye
 rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* const* kvs, const int* chunk_lens, int R,
                            const void* x, void* y, void* workspace, size_t workspace_bytes, void* stream) {
     return prefill_impl(ctx, packed, layer, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, stream);
+}
+
+rs_status rs_ctx_set_mrope_sections(rs_ctx* c, int temporal, int height, int width) {
+    if (!c) return fail(RS_EINVAL, "ctx is null");
+    if (temporal < 0 || height < 0 || width < 0 || temporal + height + width != c->cfg.head_dim / 2)
+        return fail(RS_EINVAL, "sections %d + %d + %d must be non-negative and sum to head_dim / 2 = %d", temporal, height, width,
+                    c->cfg.head_dim / 2);
+    if (temporal % 4 || height % 4 || width % 4) return fail(RS_EINVAL, "each section must be a multiple of 4 rotary pairs");
+    c->mrope_b0 = temporal;
+    c->mrope_b1 = temporal + height;
+    return RS_OK;
+}
+
+rs_status rs_prefill_batch_mrope(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* const* kvs, const int* chunk_lens,
+                                 int R, const int* positions, const void* x, void* y, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!positions) return fail(RS_EINVAL, "positions is null");
+    return prefill_impl(ctx, packed, layer, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, stream, positions);
 }
 
 rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs,

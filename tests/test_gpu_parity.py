@@ -349,6 +349,54 @@ def test_first_token_logits(hidden, vocab, n_rows):
         np.abs(np.sort(want, axis=1)[:, -1] - np.sort(want, axis=1)[:, -2]) < 1e-3 * np.abs(want).max())
 
 
+@pytest.mark.parametrize("shape_name, sections", [("tiny", (8, 12, 12)), ("small128", (16, 24, 24))])
+def test_three_axis_rotary_positions(shape_name, sections):
+    """rs_prefill_batch_mrope: image rows carry (t, h, w) grid positions, text rows equal positions on the three axes;
+    two chunks; compared with the oracle's unchunked layer using the same positions.  Then the same call with all axes
+    equal to the sequential position must reproduce rs_prefill_batch bit for bit."""
+    R = _runner()
+    shape = synth.TINY if shape_name == "tiny" else synth.LayerShape("small128", 512, 8, 2, 128, 768)
+    w = synth.layer_weights(shape, 700, qkv_bias=True, gains="uniform")
+    grid_h, grid_w = 9, 12
+    n_img, n_txt = grid_h * grid_w, 41
+    x = synth.prompt_rows([("text", 20), ("image", n_img), ("text", n_txt)], shape.hidden, 701)
+    pos = [(i, i, i) for i in range(20)]
+    pos += [(20, 20 + i // grid_w, 20 + i % grid_w) for i in range(n_img)]
+    nxt = 20 + max(grid_h, grid_w)
+    pos += [(nxt + i,) * 3 for i in range(n_txt)]
+    pos = np.asarray(pos, dtype=np.int64)
+    n = x.shape[0]
+    stack = R.LayerStack(shape, [w], max_tokens=128, max_requests=1, max_pos=256, qkv_bias=True)
+    stack.ctx.set_mrope_sections(*sections)
+    kv = stack.new_cache(n)
+    xd = _dev(x)
+    y = torch.empty_like(xd)
+    for a, b in [(0, 100), (100, n)]:
+        stack.ctx.prefill_batch_mrope(stack.layers[0], 0, [kv], [b - a], pos[a:b], xd[a:b], y[a:b], stack.ws)
+    torch.cuda.synchronize()
+    y_ref, k_ref, v_ref = layer_forward(x, LayerParams.from_arrays(shape, w), positions3=pos, sections=sections)
+    k, v = kv.export(0)
+    check(f"mrope {shape_name} Y", _np(y), y_ref)
+    check(f"mrope {shape_name} K", _np(k), k_ref)
+    check(f"mrope {shape_name} V", _np(v), v_ref)
+    # and it is NOT the 1-D result (the test would be vacuous otherwise)
+    _, k_1d, _ = layer_forward(x, LayerParams.from_arrays(shape, w))
+    assert rel_fro(_np(k), k_1d) > 0.05
+    kv1, kv2 = stack.new_cache(n), stack.new_cache(n)
+    y1, y2 = torch.empty_like(xd), torch.empty_like(xd)
+    seq = np.stack([np.arange(n)] * 3, axis=1)
+    stack.ctx.prefill_batch_mrope(stack.layers[0], 0, [kv1], [n if n <= 128 else 128], seq[:128], xd[:128], y1[:128], stack.ws)
+    stack.prefill_batch(0, [kv2], [128], xd[:128], y2[:128])
+    torch.cuda.synchronize()
+    assert torch.equal(y1[:128], y2[:128])
+    from paper_2509_24381_amd.binding import RsError
+    with pytest.raises(RsError) as e:
+        stack.ctx.prefill_batch_mrope(stack.layers[0], 0, [kv1], [1], [(0, 256, 0)], xd[:1], y1[:1], stack.ws)
+    assert e.value.status_name == "RS_ECAPACITY" and kv1.length(0) == 128
+    with pytest.raises(RsError):
+        stack.ctx.set_mrope_sections(sections[0] + 1, sections[1] - 1, sections[2])
+
+
 # ------------------------------------------------------------------ production shapes
 def test_workload2_7b_2048_budget512():
     wl = synth.workload(2)

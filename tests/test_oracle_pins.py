@@ -417,3 +417,33 @@ def test_first_token_logits_closed_form_on_one_hot_rows():
     a = oracle.first_token_logits(x, g, w, eps)
     np.testing.assert_allclose(oracle.first_token_logits(x[1:2], g, w, eps), a[1:2], rtol=1e-13)
     np.testing.assert_allclose(oracle.first_token_logits(x, g, 2.0 * w, eps), 2.0 * a, rtol=1e-13)
+
+
+def test_three_axis_rope_reduces_to_1d_and_turns_each_pair_by_its_axis():
+    """(1) equal positions on the three axes, or a single section, give the 1-D rotation (up to rounding order); (2) pair j, written
+    out as a scalar complex multiplication, turns by the position of the axis whose section holds j; (3) norms are
+    kept; (4) scores depend only on per-axis position differences."""
+    import oracle
+    rng = np.random.default_rng(88)
+    n, heads, d, theta = 9, 3, 32, 1e4
+    sections = (4, 8, 4)
+    v = rng.standard_normal((n, heads, d))
+    pos = rng.integers(0, 50, size=n)
+    same = np.stack([pos, pos, pos], axis=1)
+    np.testing.assert_allclose(oracle.rope(v, same, theta, sections), oracle.rope(v, pos, theta), rtol=1e-12, atol=1e-13)
+    p3 = rng.integers(0, 50, size=(n, 3))
+    np.testing.assert_allclose(oracle.rope(v, p3, theta, (16, 0, 0)), oracle.rope(v, p3[:, 0], theta), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(oracle.rope(v, p3, theta, (0, 0, 16)), oracle.rope(v, p3[:, 2], theta), rtol=1e-12, atol=1e-13)
+    out = oracle.rope(v, p3, theta, sections)
+    axis_of = [0] * 4 + [1] * 8 + [2] * 4
+    for t in range(n):
+        for j in range(d // 2):
+            ang = p3[t, axis_of[j]] * theta ** (-2.0 * j / d)
+            z = (v[t, 1, j] + 1j * v[t, 1, j + d // 2]) * np.exp(1j * ang)
+            assert abs(out[t, 1, j] - z.real) < 1e-12 and abs(out[t, 1, j + d // 2] - z.imag) < 1e-12
+    np.testing.assert_allclose(np.linalg.norm(out, axis=-1), np.linalg.norm(v, axis=-1), rtol=1e-13)
+    q, k = rng.standard_normal((2, n, 1, d))
+    base = np.einsum("nhd,mhd->nm", oracle.rope(q, p3, theta, sections), oracle.rope(k, p3, theta, sections))
+    shift = np.array([7, 0, 3])
+    moved = np.einsum("nhd,mhd->nm", oracle.rope(q, p3 + shift, theta, sections), oracle.rope(k, p3 + shift, theta, sections))
+    np.testing.assert_allclose(moved, base, rtol=1e-10, atol=1e-10)
