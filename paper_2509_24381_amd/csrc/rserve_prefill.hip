@@ -70,7 +70,8 @@ struct rs_ctx {
     int next_slot = 0;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
     int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
-    int attn_variant = 1;     // RS_ATTN environment variable: 1 software-pipelined attention kernel, 0 the plain one
+    int attn_variant = 1;     // RS_ATTN environment variable: 2 the wide software-pipelined attention kernel (256 rows per
+                              // workgroup), 1 the 128-row software-pipelined one, 0 the plain one
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
     // measurement hook: HIP events around every launch of one step of the layer
@@ -247,7 +248,10 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     tm.end(RS_STEP_APPEND_KV);
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
     tm.begin(RS_STEP_ATTENTION);
-    if (c->attn_variant == 1)
+    if (c->attn_variant == 2)
+        hipLaunchKernelGGL(attn_prefill_wide_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+    else if (c->attn_variant == 1)
         hipLaunchKernelGGL(attn_prefill_pipelined_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     else
@@ -334,9 +338,10 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         d.vtcache = kv->vt_of(layer);
         const int ri = (int)reqs.size();
         reqs.push_back(d);
-        const int nqb = (Ti * g + ATT_ROWS - 1) / ATT_ROWS;
+        const int item_rows = ctx->attn_variant == 2 ? ATT_WIDE_ROWS : ATT_ROWS;
+        const int nqb = (Ti * g + item_rows - 1) / item_rows;
         for (int qb = 0; qb < nqb; ++qb) {
-            const int t_max = std::min(Ti - 1, (qb * ATT_ROWS + ATT_ROWS - 1) / g);
+            const int t_max = std::min(Ti - 1, (qb * item_rows + item_rows - 1) / g);
             const int nkb = (P + t_max + 1 + ATT_KEYS - 1) / ATT_KEYS;
             for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb});
         }
@@ -527,6 +532,8 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     // (the pipelined attention kernel keeps its LDS in static arrays; these references make the launch stubs exist)
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
     *out = c;
     return RS_OK;

@@ -196,6 +196,28 @@ def oracle_batch(shape, w, reqs):
     return y, [(s.k, s.v) for s in states]
 
 
+@pytest.mark.parametrize("shape_name", ["tiny", "small128"])
+def test_attention_maxima_growing_along_the_cache(shape_name):
+    """Prior keys whose magnitude grows ninefold along the cache: every query's largest score keeps rising from tile to
+    tile, by more than 2^8 in total, so the attention kernel has to move its reference maximum and rescale what it has
+    accumulated well after a request's first tiles (with random inputs that happens in the first tile only)."""
+    shape = synth.TINY if shape_name == "tiny" else synth.LayerShape("small128", 256, 4, 2, 128, 512)
+    w = synth.layer_weights(shape, 91)
+    w.wd = np.zeros_like(w.wd)            # y = x + attention @ W_o^T: nothing hides the attention term
+    rng = np.random.default_rng(92)
+    prior, t_new = 1536, 200
+    grow = (1.0 + 8.0 * np.arange(prior, dtype=np.float32) / prior)[:, None, None]
+    scale = 1.0 if shape.head_dim == 64 else 1.4   # same score spread for both head sizes
+    pk = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32) * grow * scale)
+    pv = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+    rows = synth.prompt_rows([("text", t_new)], shape.hidden, 93)
+    reqs = [synth.BatchRequest(prior, pk, pv, rows)]
+    y, _ = run_batch(shape, w, reqs, capacity=prior + 256)
+    y_ref, _ = oracle_batch(shape, w, reqs)
+    check(f"{shape_name} y, growing maxima", y, y_ref)
+    check(f"{shape_name} attention term, growing maxima", y - rows, y_ref - rows, tol=3e-2)
+
+
 def test_small_ragged_batch_with_empty_and_single_row_requests():
     shape = synth.TINY
     w = synth.layer_weights(shape, 77, gains="uniform")
