@@ -10,8 +10,20 @@
 // halves 512 bytes apart, tokens 16 bytes apart (rows of the last block past `rows` are left untouched: they are never
 // used).  One workgroup handles 8 tokens: 32 threads read 512 contiguous bytes of one token per step, and the 8 tokens'
 // 16-byte chunks of one (k-step, half) land in 128 contiguous bytes (one cache line).
+// Workgroups past the row blocks copy the call's descriptors (requests, attention work items, cache blocks, row
+// positions) from the pinned host buffer the library filled, which the device reads in place, into the workspace: the
+// later kernels of the call then find them in device memory, and no copy command sits between two calls (a runtime copy
+// of a few tens of KB costs a blit kernel of 13 us plus the gaps around it).
 __global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16* __restrict__ x, bf16* __restrict__ dst,
-                                                                     float* __restrict__ inv_rms, int rows, int H, float eps) {
+                                                                     float* __restrict__ inv_rms, int rows, int H, float eps,
+                                                                     const uint4* __restrict__ desc_src,
+                                                                     uint4* __restrict__ desc_dst, int desc_chunks) {
+    const int row_blocks = (rows + 7) >> 3;
+    if ((int)blockIdx.x >= row_blocks) {
+        const int i = ((int)blockIdx.x - row_blocks) * 256 + (int)threadIdx.x;
+        if (i < desc_chunks) desc_dst[i] = desc_src[i];
+        return;
+    }
     const int r = threadIdx.x >> 5, c = threadIdx.x & 31;
     const int m = blockIdx.x * 8 + r;
     const int mc = min(m, rows - 1);  // threads of rows past the end follow along (their shuffles are needed) and store nothing

@@ -64,6 +64,7 @@ struct rs_ctx {
     float2* rope_dev = nullptr;  // [max_pos][d/2] (cos, sin)
     // pinned staging ring for per-call descriptors
     char* pinned[RING_SLOTS] = {};
+    char* pinned_dev[RING_SLOTS] = {};  // the same buffers as the device addresses them
     hipEvent_t slot_done[RING_SLOTS] = {};
     bool slot_used[RING_SLOTS] = {};
     size_t slot_bytes = 0;
@@ -367,10 +368,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(KVBlockItem) * vbs.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks, rowpos.data(), sizeof(int) * rowpos.size());
     char* wsb = reinterpret_cast<char*>(ws);
-    RS_HIP(hipMemcpyAsync(wsb + L.desc, stage, ds.total, hipMemcpyHostToDevice, st));
-    RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
-    ctx->slot_used[slot] = true;
-    ctx->next_slot = (slot + 1) % RING_SLOTS;
+    // (the first kernel below copies the staged descriptors into the workspace; the slot is free again once it has run)
     const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
     const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
     const KVBlockItem* d_vb = reinterpret_cast<const KVBlockItem*>(wsb + L.desc + ds.reqs + ds.items);
@@ -394,8 +392,14 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     // 1/rms of every input row (the first RMSNorm; its gain lives in the packed W_qkv)
     tm.begin(RS_STEP_ROW_RMS);
     // and, in the same pass, x in the GEMMs' fragment-major token-operand layout
-    hipLaunchKernelGGL(rms_and_fragment_major_kernel, dim3((T + 7) / 8), dim3(256), 0, st, xb, xf, inv_rms1, T, H, f.rms_eps);
+    const int desc_chunks = (int)(ds.total / 16);
+    hipLaunchKernelGGL(rms_and_fragment_major_kernel, dim3((T + 7) / 8 + (desc_chunks + 255) / 256), dim3(256), 0, st, xb, xf,
+                       inv_rms1, T, H, f.rms_eps, reinterpret_cast<const uint4*>(ctx->pinned_dev[slot]),
+                       reinterpret_cast<uint4*>(wsb + L.desc), desc_chunks);
     RS_HIP(hipGetLastError());
+    RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
+    ctx->slot_used[slot] = true;
+    ctx->next_slot = (slot + 1) % RING_SLOTS;
     tm.end(RS_STEP_ROW_RMS);
     // qkv = rope( (x Wqkv'^T) / rms + b )
     tm.begin(RS_STEP_QKV_GEMM);
@@ -511,6 +515,8 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     for (int i = 0; i < RING_SLOTS; ++i) {
         e = hipHostMalloc((void**)&c->pinned[i], c->slot_bytes, hipHostMallocDefault);
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipHostMalloc: %s", hipGetErrorString(e)));
+        e = hipHostGetDevicePointer((void**)&c->pinned_dev[i], c->pinned[i], 0);
+        if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)));
         e = hipEventCreateWithFlags(&c->slot_done[i], hipEventDisableTiming);
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
     }
