@@ -136,7 +136,10 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    stack.ctx.profile_enable("gate_up_gemm", calls_per_step * args.steps)
+    # every third gate/up launch is bracketed by events (all of them when a step is a single call): the samples walk
+    # through all layers and chunk positions, and two thirds of the launches keep their neighbours close
+    gu_every = 3 if calls_per_step > 1 else 1
+    stack.ctx.profile_enable("gate_up_gemm", calls_per_step * args.steps, every=gu_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):

@@ -196,6 +196,10 @@ typedef enum rs_step {
  * the summed elapsed milliseconds and the number of launches measured, and restarts the count.  Events are created in
  * rs_profile_enable, never inside rs_prefill_*. */
 rs_status rs_profile_enable(rs_ctx* ctx, int step, int max_launches);
+/* Only every `every`-th launch of the step is bracketed (1, the initial setting: all of them).  The two event records
+ * around a kernel keep it from overlapping its neighbours' launch and drain (about 5 us each); sampling keeps a
+ * measurement inside a timed region from slowing that region.  Persists until changed. */
+rs_status rs_profile_sample_every(rs_ctx* ctx, int every);
 rs_status rs_profile_read(rs_ctx* ctx, double* total_ms, int* launches);
 
 /* Message of the most recent failing call on this thread (never NULL). */

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
-    "rs_profile_enable", "rs_profile_read",
+    "rs_profile_enable", "rs_profile_sample_every", "rs_profile_read",
 )
 
 SCHED_SYMBOLS = (
@@ -108,6 +108,7 @@ def load_library():
         "rs_last_error": (C.c_char_p, []),
         "rs_version": (i, []),
         "rs_profile_enable": (i, [vp, i, i]),
+        "rs_profile_sample_every": (i, [vp, i]),
         "rs_profile_read": (i, [vp, C.POINTER(C.c_double), C.POINTER(i)]),
         "rs_sched_create": (i, [i, C.POINTER(vp)]),
         "rs_sched_destroy": (None, [vp]),
@@ -275,9 +276,10 @@ class Context:
         return torch.empty(self.workspace_bytes(max_tokens, max_requests), dtype=torch.uint8, device="cuda")
 
     # ---- measurement hook
-    def profile_enable(self, step, max_launches: int = 1024):
-        """step: a name from STEPS, its index, or None / -1 to switch the hook off."""
+    def profile_enable(self, step, max_launches: int = 1024, every: int = 1):
+        """step: a name from STEPS, its index, or None / -1 to switch the hook off; every: measure each n-th launch."""
         idx = -1 if step is None else (STEPS.index(step) if isinstance(step, str) else int(step))
+        _check(self.lib.rs_profile_sample_every(self.handle, every))
         _check(self.lib.rs_profile_enable(self.handle, idx, max_launches))
 
     def profile_read(self):

@@ -78,6 +78,9 @@ struct rs_ctx {
     // measurement hook: HIP events around every launch of one step of the layer
     int prof_step = -1;
     int prof_count = 0;
+    int prof_every = 1;       // measure every n-th launch of the step
+    int prof_seen = 0;        // launches of the step seen since rs_profile_enable
+    bool prof_take = false;   // the launch in progress is being measured
     std::vector<hipEvent_t> prof_events;  // (start, stop) pairs
 };
 
@@ -225,15 +228,16 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf1
 struct StepTimer {
     rs_ctx* c;
     hipStream_t st;
-    bool on(int step) const { return c->prof_step == step && 2 * (c->prof_count + 1) <= (int)c->prof_events.size(); }
     void begin(int step) const {
-        if (on(step)) (void)hipEventRecord(c->prof_events[2 * c->prof_count], st);
+        if (c->prof_step != step) return;
+        c->prof_take = (c->prof_seen++ % c->prof_every == 0) && 2 * (c->prof_count + 1) <= (int)c->prof_events.size();
+        if (c->prof_take) (void)hipEventRecord(c->prof_events[2 * c->prof_count], st);
     }
     void end(int step) const {
-        if (on(step)) {
-            (void)hipEventRecord(c->prof_events[2 * c->prof_count + 1], st);
-            ++c->prof_count;
-        }
+        if (c->prof_step != step || !c->prof_take) return;
+        (void)hipEventRecord(c->prof_events[2 * c->prof_count + 1], st);
+        ++c->prof_count;
+        c->prof_take = false;
     }
 };
 
@@ -721,11 +725,20 @@ rs_status rs_profile_enable(rs_ctx* c, int step, int max_launches) {
     if (step >= 0 && !c->has_device) return fail(RS_EHIP, "no HIP device");
     c->prof_step = step;
     c->prof_count = 0;
+    c->prof_seen = 0;
+    c->prof_take = false;
     while (step >= 0 && (int)c->prof_events.size() < 2 * max_launches) {
         hipEvent_t e;
         RS_HIP(hipEventCreate(&e));
         c->prof_events.push_back(e);
     }
+    return RS_OK;
+}
+
+rs_status rs_profile_sample_every(rs_ctx* c, int every) {
+    if (!c) return fail(RS_EINVAL, "ctx is null");
+    if (every <= 0) return fail(RS_EINVAL, "every = %d must be positive", every);
+    c->prof_every = every;
     return RS_OK;
 }
 

@@ -104,6 +104,19 @@ def test_sizes_and_kv_bookkeeping(lib):
     assert b"" != lib.rs_last_error()
 
 
+def test_profile_hook_argument_checks(lib):
+    ctx = Context(tiny_cfg())
+    assert lib.rs_profile_sample_every(ctx.handle, 0) == -1
+    assert lib.rs_profile_sample_every(ctx.handle, -3) == -1
+    assert lib.rs_profile_sample_every(None, 2) == -1
+    assert lib.rs_profile_sample_every(ctx.handle, 3) == 0
+    assert lib.rs_profile_enable(ctx.handle, 99, 4) == -1        # no such step
+    assert lib.rs_profile_enable(ctx.handle, 0, 0) == -1         # nothing to measure
+    assert lib.rs_profile_enable(ctx.handle, -1, 0) == 0         # switching the hook off needs no device
+    ms, n = ctx.profile_read()
+    assert (ms, n) == (0.0, 0)
+
+
 def test_prefill_argument_checks_happen_before_any_launch(lib):
     ctx = Context(tiny_cfg())
     other = Context(tiny_cfg())

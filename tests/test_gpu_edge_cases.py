@@ -158,6 +158,35 @@ def test_batch_at_request_limit_with_mixed_capacities_is_order_equivariant():
         off += lens[i]
 
 
+def test_profile_hook_counts_and_samples_launches():
+    """rs_profile_enable brackets a step's launches with events; rs_profile_sample_every thins them out; neither changes
+    the result."""
+    r = R()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 41)
+    x = r.to_device_bf16(synth.prompt_rows([("text", 256)], shape.hidden, 42))
+    stack = r.LayerStack(shape, [w], max_tokens=64, max_requests=1, max_pos=256)
+    chunks = [(0, 64), (64, 128), (128, 192), (192, 256)]
+
+    def run(step, every):
+        kv = stack.new_cache(256)
+        stack.ctx.profile_enable(step, 16, every=every)
+        y = stack.prefill_prompt(x, chunks, kv)
+        torch.cuda.synchronize()
+        ms, n = stack.ctx.profile_read()
+        stack.ctx.profile_enable(None)
+        return r.to_numpy_f32(y), ms, n
+
+    y0, ms0, n0 = run(None, 1)
+    assert (ms0, n0) == (0.0, 0)
+    y1, ms1, n1 = run("gate_up_gemm", 1)
+    assert n1 == 4 and ms1 > 0.0
+    y2, ms2, n2 = run("attention", 3)       # launches 0 and 3 of the four
+    assert n2 == 2 and ms2 > 0.0
+    np.testing.assert_array_equal(y1, y0)
+    np.testing.assert_array_equal(y2, y0)
+
+
 def test_export_import_round_trip_is_bit_exact():
     r = R()
     shape = synth.LayerShape("s128", 256, 2, 1, 128, 256)
