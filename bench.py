@@ -75,6 +75,7 @@ def main():
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
                     help="which of the five synthetic workloads to time (default 3: the headline configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
+    ap.add_argument("--paged", action="store_true", help="keep the KV caches in pages of 64 tokens taken from one pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline sample is sized for")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -105,8 +106,9 @@ def main():
         priors = [r.prior_len for r in reqs]
         stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=len(reqs), max_pos=wl.max_prior + wl.budget)
         kvs = []
+        pool = stack.new_pool(sum((r.prior_len + r.rows.shape[0] + 63) // 64 for r in reqs)) if args.paged else None
         for r in reqs:
-            kv = stack.new_cache(wl.max_prior + wl.budget)
+            kv = pool.new_cache(1) if args.paged else stack.new_cache(wl.max_prior + wl.budget)
             if r.prior_len:
                 kv.import_(0, runner.to_device_bf16(r.prior_k), runner.to_device_bf16(r.prior_v))
             kvs.append(kv)
@@ -123,7 +125,8 @@ def main():
         x = wl.prompt()
         chunks = wl.chunks()
         stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=1, max_pos=wl.n_tokens)
-        kv = stack.new_cache(wl.n_tokens)
+        pool = stack.new_pool(wl.n_layers * ((wl.n_tokens + 63) // 64)) if args.paged else None
+        kv = pool.new_cache(wl.n_layers) if args.paged else stack.new_cache(wl.n_tokens)
         x_dev = runner.to_device_bf16(x)
         call_shapes = [(b - a, a) for a, b in chunks]
         n_tokens, calls_per_step = wl.n_tokens, len(chunks) * wl.n_layers
@@ -170,7 +173,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.n_layers, "tokens_per_step": n_tokens, "token_budget": wl.budget,
-                   "calls_per_step": calls_per_step,
+                   "calls_per_step": calls_per_step, "kv_cache": "paged (64-token pages)" if args.paged else "contiguous",
                    "shape": f"hidden {sh.hidden}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, head_dim {sh.head_dim}, "
                             f"mlp {sh.mlp_inter}"},
         "tflops": tflops,

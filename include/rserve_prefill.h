@@ -99,7 +99,7 @@ rs_status rs_weights_pack(rs_ctx* ctx, const rs_layer_weights* src, void* dst, s
                           rs_layer_weights* packed, void* hip_stream);
 
 /* KV cache (the per-request state chunked prefill builds, section 2.2.1).  The slab layout is private; capacity is
- * fixed at allocation.  Each layer keeps its own length so that layers 0..L-1 can be run in turn for a chunk.
+ * fixed at allocation (see below for caches that grow page by page).  Each layer keeps its own length so that layers 0..L-1 can be run in turn for a chunk.
  *   rs_kv_bytes      bytes of device memory needed for n_layers layers of capacity_tokens tokens.
  *   rs_kv_alloc      wraps caller-owned device memory `dev_mem` (>= rs_kv_bytes, 256-byte aligned); lengths start at 0.
  *   rs_kv_free       frees the host handle only.
@@ -117,6 +117,30 @@ rs_status rs_kv_reset(rs_kv* kv);
 rs_status rs_kv_truncate(rs_kv* kv, int layer, int n_tokens);
 rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out_dev, void* v_out_dev, void* hip_stream);
 rs_status rs_kv_import(rs_kv* kv, int layer, const void* k_dev, const void* v_dev, int n_tokens, void* hip_stream);
+
+/* Paged, growable KV caches.  The serving systems the paper measures size their KV memory as the largest that fits
+ * (section 4.1.3), which presupposes that requests share it in small units instead of reserving a maximum length each.
+ * A pool cuts caller-owned device memory into pages of rs_kv_page_bytes() bytes; a page holds 64 tokens of ONE layer
+ * (K and V of all KV heads).  A paged cache starts empty and takes pages from its pool as tokens arrive: inside
+ * rs_prefill_* and rs_kv_import, after every check has passed (a call that would need more pages than the pool has free
+ * fails with RS_ECAPACITY before anything is launched or changed; rs_prefill_model_batch counts the pages of all its
+ * layers together).  rs_kv_truncate and rs_kv_reset give whole pages beyond the new length back, rs_kv_free all of them.
+ * Everything else (rs_kv_len, export, import, every rs_prefill_* entry point, mixing paged and contiguous caches in one
+ * micro-batch) works alike for both kinds, and the results are bit-identical to those with a contiguous cache.
+ * rs_kv_capacity of a paged cache is the number of tokens its current pages can hold (the smallest over its layers).
+ *   rs_kv_pool_create   dev_mem: 256-byte aligned device memory of `bytes` bytes, used as floor(bytes / page) pages;
+ *                       RS_EWORKSPACE if that is not even one page.  The memory need not be initialised.
+ *   rs_kv_pool_destroy  frees the host handle; RS_ESTATE while caches allocated from the pool are alive.
+ *   rs_kv_pool_pages / rs_kv_pool_free_pages   total and currently free pages (-1 for a null pool).
+ *   rs_kv_alloc_paged   an empty cache of n_layers layers on `pool` (free it with rs_kv_free before the pool).
+ * The host bookkeeping is not thread-safe: one thread at a time per pool. */
+typedef struct rs_kv_pool rs_kv_pool;
+size_t rs_kv_page_bytes(const rs_ctx* ctx);
+rs_status rs_kv_pool_create(rs_ctx* ctx, void* dev_mem, size_t bytes, rs_kv_pool** out);
+rs_status rs_kv_pool_destroy(rs_kv_pool* pool);
+int rs_kv_pool_pages(const rs_kv_pool* pool);
+int rs_kv_pool_free_pages(const rs_kv_pool* pool);
+rs_status rs_kv_alloc_paged(rs_ctx* ctx, rs_kv_pool* pool, int n_layers, rs_kv** out);
 
 /* Bytes of device workspace a call with up to max_tokens rows and max_requests requests needs. */
 size_t rs_workspace_bytes(const rs_ctx* ctx, int max_tokens, int max_requests);

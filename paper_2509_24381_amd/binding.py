@@ -21,6 +21,8 @@ STATUS = {0: "RS_OK", -1: "RS_EINVAL", -2: "RS_ECAPACITY", -3: "RS_EWORKSPACE", 
 EXPORTED_SYMBOLS = (
     "rs_ctx_create", "rs_ctx_destroy", "rs_weights_packed_bytes", "rs_weights_pack", "rs_kv_bytes", "rs_kv_alloc",
     "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
+    "rs_kv_page_bytes", "rs_kv_pool_create", "rs_kv_pool_destroy", "rs_kv_pool_pages", "rs_kv_pool_free_pages",
+    "rs_kv_alloc_paged",
     "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
@@ -97,6 +99,12 @@ def load_library():
         "rs_kv_truncate": (i, [vp, i, i]),
         "rs_kv_export": (i, [vp, i, vp, vp, vp]),
         "rs_kv_import": (i, [vp, i, vp, vp, i, vp]),
+        "rs_kv_page_bytes": (sz, [vp]),
+        "rs_kv_pool_create": (i, [vp, vp, sz, C.POINTER(vp)]),
+        "rs_kv_pool_destroy": (i, [vp]),
+        "rs_kv_pool_pages": (i, [vp]),
+        "rs_kv_pool_free_pages": (i, [vp]),
+        "rs_kv_alloc_paged": (i, [vp, vp, i, C.POINTER(vp)]),
         "rs_workspace_bytes": (sz, [vp, i, i]),
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
@@ -178,13 +186,48 @@ class PackedWeights:
         self.struct = struct
 
 
-class KVCache:
-    """One request's KV cache over n_layers layers; owns the device slab and the host handle."""
+class KVPool:
+    """A pool of KV pages (64 tokens of one layer each) in one device slab; paged caches take their pages from it."""
 
-    def __init__(self, ctx: "Context", handle: int, slab):
+    def __init__(self, ctx: "Context", n_pages: int):
+        import torch
+        self.ctx = ctx
+        self.page_bytes = ctx.lib.rs_kv_page_bytes(ctx.handle)
+        self.slab = torch.empty(max(n_pages * self.page_bytes, 256), dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(ctx.lib.rs_kv_pool_create(ctx.handle, _ptr(self.slab), n_pages * self.page_bytes, C.byref(h)))
+        self.handle = h
+
+    def __del__(self):
+        try:
+            if self.handle:
+                load_library().rs_kv_pool_destroy(self.handle)   # refuses (and leaks the handle) while caches are alive
+                self.handle = None
+        except Exception:
+            pass
+
+    @property
+    def pages(self) -> int:
+        return load_library().rs_kv_pool_pages(self.handle)
+
+    @property
+    def free_pages(self) -> int:
+        return load_library().rs_kv_pool_free_pages(self.handle)
+
+    def new_cache(self, n_layers: int) -> "KVCache":
+        h = C.c_void_p()
+        _check(self.ctx.lib.rs_kv_alloc_paged(self.ctx.handle, self.handle, n_layers, C.byref(h)))
+        return KVCache(self.ctx, h.value, self.slab, pool=self)
+
+
+class KVCache:
+    """One request's KV cache over n_layers layers; holds the device slab (its own, or its pool's) and the host handle."""
+
+    def __init__(self, ctx: "Context", handle: int, slab, pool: "KVPool" = None):
         self.ctx = ctx
         self.handle = C.c_void_p(handle)
         self.slab = slab
+        self.pool = pool          # keeps the pool alive as long as the cache
 
     def __del__(self):
         try:

@@ -16,8 +16,9 @@
 //
 // Cache layout (private to the library): K is [Hkv][capacity][d]; V is stored transposed in blocks of 64 tokens,
 // [Hkv][capacity/64][d][64], so that a V^T tile is one contiguous 64*d*2-byte run with the key index innermost,
-// which is what the MFMA A operand needs.  Positions >= len inside the last V block hold zeros (the append and
-// import kernels maintain this), so masked probabilities (exact zeros) never meet NaN bit patterns.
+// which is what the MFMA A operand needs.  A paged cache keeps the same 64-token tiles, gathered per page instead of per
+// plane (see KVHeadTiles).  Positions >= len inside the last V block hold zeros (the append and import kernels
+// maintain this), so masked probabilities (exact zeros) never meet NaN bit patterns.
 #pragma once
 #include "common.h"
 
@@ -25,10 +26,63 @@ struct ReqDesc {
     int row0;       // first row of this request in the packed [sum T, ...] activations
     int T;          // rows this call
     int P;          // tokens already cached before this call
-    int cap;        // capacity (tokens, multiple of 64) of this request's cache
-    bf16* kcache;   // this layer's K  [Hkv][cap][d]
-    bf16* vtcache;  // this layer's V^T [Hkv][cap/64][d][64]
+    int cap;        // capacity (tokens, multiple of 64) of this request's cache (contiguous caches)
+    bf16* kcache;   // contiguous: this layer's K [Hkv][cap][d];  paged: the pool's first page
+    bf16* vtcache;  // contiguous: this layer's V^T [Hkv][cap/64][d][64];  paged: unused
+    const int* pages;  // paged: pages[b] = pool page that holds this layer's 64-token block b;  contiguous: null
+    int hkv;           // KV heads (a page is [Hkv] K tiles followed by [Hkv] V^T tiles)
+    int pad_;
 };
+
+// Where the 64-token tiles of one KV head live.  A tile is K rows [64][d] or V^T [d][64], either one contiguous run of
+// 64*D*2 bytes, at  base + index * stride:  in a contiguous cache both planes are arrays of tiles [kvh][block], so the
+// index is the block and the stride one tile; in a paged cache the index is the block's page (looked up in the request's
+// table, a uniform load) and the stride one page, which holds the K tiles of all heads followed by their V^T tiles.
+// Set up once per workgroup, so that a tile's address costs one multiply-add in the loop whatever the kind of cache.
+struct KVHeadTiles {
+    char* k_base;
+    char* v_base;
+    uint32_t stride;
+    const int* pages;
+    // MAY_PAGE = false is for kernels launched only when every cache of the call is contiguous: no lookup, and nothing
+    // in the loop that the compiler cannot see to be uniform (the software-pipelined attention kernel loses a tenth of
+    // its speed to the few extra instructions otherwise).
+    // The index of a block: may be called long before the address is needed (the lookup's latency then passes unseen).
+    template <bool MAY_PAGE = true>
+    __device__ __forceinline__ int index_of(int block) const {
+        if constexpr (!MAY_PAGE) return block;
+        return pages == nullptr ? block : pages[block];
+    }
+    // (the index is the same for the whole wavefront; saying so here, where the value is used and not where it was
+    // loaded, keeps the address in scalar registers, which the buffer resource of an LDS-DMA load needs)
+    template <bool MAY_PAGE = true>
+    __device__ __forceinline__ char* k_tile(int index) const {
+        if constexpr (!MAY_PAGE) return k_base + (size_t)(uint32_t)index * stride;
+        return k_base + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(index) * stride;
+    }
+    template <bool MAY_PAGE = true>
+    __device__ __forceinline__ char* v_tile(int index) const {
+        if constexpr (!MAY_PAGE) return v_base + (size_t)(uint32_t)index * stride;
+        return v_base + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(index) * stride;
+    }
+};
+template <int D>
+RS_DEVICE KVHeadTiles kv_head_tiles(const ReqDesc& rq, int kvh) {
+    constexpr uint32_t TILE = 64u * D * 2u;
+    KVHeadTiles t;
+    t.pages = rq.pages;
+    if (rq.pages == nullptr) {
+        const size_t head = (size_t)kvh * (size_t)(rq.cap >> 6) * TILE;
+        t.k_base = reinterpret_cast<char*>(rq.kcache) + head;
+        t.v_base = reinterpret_cast<char*>(rq.vtcache) + head;
+        t.stride = TILE;
+    } else {
+        t.k_base = reinterpret_cast<char*>(rq.kcache) + (size_t)kvh * TILE;
+        t.v_base = reinterpret_cast<char*>(rq.kcache) + (size_t)(rq.hkv + kvh) * TILE;
+        t.stride = 2u * (uint32_t)rq.hkv * TILE;
+    }
+    return t;
+}
 
 struct AttnItem {
     int req;
@@ -65,7 +119,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
 
     const AttnItem item = items[blockIdx.x];
     const ReqDesc rq = reqs[item.req];
-    const int cap = rq.cap;
     const int rows_total = rq.T * g;
     const int row = item.qblock * ATT_ROWS + wave * 32 + l32;
     const int row_c = min(row, rows_total - 1);
@@ -87,8 +140,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
     }
 
     // ---- tile loader: both tiles are contiguous TILE_BYTES runs in the cache
-    const char* ksrc = reinterpret_cast<const char*>(rq.kcache + (size_t)item.kvh * cap * D);
-    const char* vsrc = reinterpret_cast<const char*>(rq.vtcache + (size_t)item.kvh * (cap / ATT_KEYS) * D * ATT_KEYS);
     uint32_t k_src_off[LOADS], v_src_off[LOADS];
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
@@ -105,12 +156,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
         }
     }
     uint4 rk[LOADS], rv[LOADS];
+    const KVHeadTiles tiles = kv_head_tiles<D>(rq, item.kvh);
     auto load_tile = [&](int kb) {
-        const size_t tb = (size_t)kb * TILE_BYTES;
+        const int idx = tiles.index_of(kb);
+        const char* ksrc = tiles.k_tile(idx);
+        const char* vsrc = tiles.v_tile(idx);
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) rk[i] = ld_global_16(ksrc + tb + k_src_off[i]);
+        for (int i = 0; i < LOADS; ++i) rk[i] = ld_global_16(ksrc + k_src_off[i]);
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) rv[i] = ld_global_16(vsrc + tb + v_src_off[i]);
+        for (int i = 0; i < LOADS; ++i) rv[i] = ld_global_16(vsrc + v_src_off[i]);
     };
     auto park_tile = [&](int buf) {
         char* ks = smem + buf * (2 * TILE_BYTES);
@@ -258,7 +312,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
 // iteration kb-1 finished with.  The four buffers are separate LDS objects so that the compiler can tell that the
 // fragment reads of an iteration do not touch the buffers being filled; it waits for the DMA at the barrier that ends
 // the iteration.
-template <int D>
+template <int D, bool MAY_PAGE>
 __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const ReqDesc* __restrict__ reqs,
                                                                         const AttnItem* __restrict__ items,
                                                                         const bf16* __restrict__ qkv, int ld_qkv,
@@ -282,7 +336,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
 
     const AttnItem item = items[blockIdx.x];
     const ReqDesc rq = reqs[item.req];
-    const int cap = rq.cap;
     const int rows_total = rq.T * g;
     const int row = item.qblock * ATT_ROWS + wave * 32 + l32;
     const int row_c = min(row, rows_total - 1);
@@ -303,9 +356,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     //      fills LDS bytes [(i*256 + wave*64)*16, +1 KB) linearly by lane, each lane fetching the 16-byte chunk that
     //      belongs in its (swizzled) place.  Tiles past the item's last one are not fetched.
     const int nkb = item.nkb;
-    const int head_bytes = cap * D * 2;  // one KV head's K (or V^T) region
-    char* const k_head = reinterpret_cast<char*>(rq.kcache) + (size_t)item.kvh * head_bytes;
-    char* const v_head = reinterpret_cast<char*>(rq.vtcache) + (size_t)item.kvh * head_bytes;
     uint32_t k_src_off[4], v_src_off[4];  // (fixed bound: LOADS <= 4; a template-dependent bound breaks the host-side stub)
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
@@ -321,22 +371,27 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
             v_src_off[i] = (uint32_t)(r * 128 + c * 16);
         }
     }
-    auto fetch_k = [&](char* buf, int kb) {
+    // (the page of a tile is looked up one iteration before the tile is fetched: see the iteration)
+    const KVHeadTiles tiles = kv_head_tiles<D>(rq, item.kvh);
+    auto page_of = [&](int kb) { return kb < nkb ? tiles.template index_of<MAY_PAGE>(kb) : 0; };
+    auto fetch_k = [&](char* buf, int kb, int page) {
         if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)k_head, 0, head_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rk =
+                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.template k_tile<MAY_PAGE>(page), 0, TILE_BYTES, 0x00020000);
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, k_src_off[i],
-                                                         kb * TILE_BYTES, 0, 0);
+                                                         0, 0, 0);
         }
     };
-    auto fetch_v = [&](char* buf, int kb) {
+    auto fetch_v = [&](char* buf, int kb, int page) {
         if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)v_head, 0, head_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rv =
+                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.template v_tile<MAY_PAGE>(page), 0, TILE_BYTES, 0x00020000);
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, v_src_off[i],
-                                                         kb * TILE_BYTES, 0, 0);
+                                                         0, 0, 0);
         }
     };
 
@@ -397,9 +452,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     };
 
     // ---- prologue: K(0), V(0), K(1) into LDS; scores and maximum of tile 0
-    fetch_k(k_buf0, 0);
-    fetch_v(v_buf0, 0);
-    fetch_k(k_buf1, 1);
+    int pg_v = page_of(1);   // page of block kb + 1 (V is fetched one tile behind K)
+    int pg_k = page_of(2);   // page of block kb + 2
+    {
+        const int pg0 = page_of(0);
+        fetch_k(k_buf0, 0, pg0);
+        fetch_v(v_buf0, 0, pg0);
+        fetch_k(k_buf1, 1, pg_v);
+    }
     __syncthreads();
     f32x16 sA[2], sB[2];
     zero_scores(sA);
@@ -414,8 +474,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     // k_next holds K(kb+1), v_cur V(kb); k_fill (= K(kb)'s buffer) receives K(kb+2), v_fill (= V(kb-1)'s) V(kb+1).
     auto iteration = [&](int kb, f32x16 (&scur)[2], f32x16 (&snext)[2], const char* k_next, char* k_fill, const char* v_cur,
                          char* v_fill) {
-        fetch_k(k_fill, kb + 2);
-        fetch_v(v_fill, kb + 1);
+        fetch_k(k_fill, kb + 2, pg_k);
+        fetch_v(v_fill, kb + 1, pg_v);
+        pg_v = pg_k;
+        pg_k = page_of(kb + 3);  // needed in the next iteration: the lookup's latency passes behind this one
         const float mb = m_run * scale_log2e;
         // ---- phase 1: P(kb) = exp2(S(kb) c - m c), its row sum and bf16 form.  Behind each of the 2*KSTEPS score MFMAs of
         //      tile kb+1 go the exponentials of 32 / (2*KSTEPS) scores of tile kb; scheduling fences keep that order, and
@@ -600,7 +662,6 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_wide_kernel(const ReqDesc
 
     const AttnItem item = items[blockIdx.x];
     const ReqDesc rq = reqs[item.req];
-    const int cap = rq.cap;
     const int rows_total = rq.T * g;
     int row[NQ], tok[NQ], head[NQ], qpos[NQ];
 #pragma unroll
@@ -624,9 +685,6 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_wide_kernel(const ReqDesc
 
     // ---- tile loader (as in the kernel above)
     const int nkb = item.nkb;
-    const int head_bytes = cap * D * 2;
-    char* const k_head = reinterpret_cast<char*>(rq.kcache) + (size_t)item.kvh * head_bytes;
-    char* const v_head = reinterpret_cast<char*>(rq.vtcache) + (size_t)item.kvh * head_bytes;
     uint32_t k_src_off[4], v_src_off[4];  // (fixed bound: LOADS <= 4)
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
@@ -642,22 +700,25 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_wide_kernel(const ReqDesc
             v_src_off[i] = (uint32_t)(r * 128 + c * 16);
         }
     }
+    const KVHeadTiles tiles = kv_head_tiles<D>(rq, item.kvh);
     auto fetch_k = [&](char* buf, int kb) {
         if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)k_head, 0, head_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rk =
+                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.k_tile(tiles.index_of(kb)), 0, TILE_BYTES, 0x00020000);
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, k_src_off[i],
-                                                         kb * TILE_BYTES, 0, 0);
+                                                         0, 0, 0);
         }
     };
     auto fetch_v = [&](char* buf, int kb) {
         if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)v_head, 0, head_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rv =
+                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.v_tile(tiles.index_of(kb)), 0, TILE_BYTES, 0x00020000);
 #pragma unroll
             for (int i = 0; i < LOADS; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, v_src_off[i],
-                                                         kb * TILE_BYTES, 0, 0);
+                                                         0, 0, 0);
         }
     };
 

@@ -161,6 +161,9 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const bf16* __restrict__
     const int k_col = (Hq + c) * D;
     const int v_col = (Hq + Hkv + c) * D;
     constexpr int CPR = D / 8;  // 16-byte chunks per row
+    const KVHeadTiles tiles = kv_head_tiles<D>(rq, c);
+    const int tile_index = tiles.index_of(it.block);
+    bf16* const k_tile = reinterpret_cast<bf16*>(tiles.k_tile(tile_index));
     for (int idx = threadIdx.x; idx < 64 * CPR; idx += blockDim.x) {
         const int kk = idx / CPR, ch = idx - kk * CPR;
         const int pos = tok0 + kk;
@@ -170,12 +173,12 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const bf16* __restrict__
             const bf16* row = qkv + (size_t)(rq.row0 + pos - rq.P) * ld_qkv + ch * 8;
             k = ld_global_16(row + k_col);
             v = ld_global_16(row + v_col);
-            st_global_16(rq.kcache + ((size_t)c * rq.cap + pos) * D + ch * 8, k);
+            st_global_16(k_tile + (size_t)kk * D + ch * 8, k);
         }
         *reinterpret_cast<uint4*>(&tile[kk][ch * 8]) = v;  // zeros for positions outside [P, P+T)
     }
     __syncthreads();
-    bf16* dst = rq.vtcache + ((size_t)c * (rq.cap / 64) + it.block) * D * 64;
+    bf16* dst = reinterpret_cast<bf16*>(tiles.v_tile(tile_index));
     // thread -> (feature dd, group of 8 tokens): gathers the 8 tokens' values of feature dd and stores them as one chunk
     for (int idx = threadIdx.x; idx < D * 8; idx += blockDim.x) {
         const int dd = idx >> 3, g8 = idx & 7;
@@ -227,32 +230,51 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const bf16* __restrict__
 }
 
 // ---------------------------------------------------------------- cache export / import (canonical [tokens][Hkv][d])
+// The cache is described like a request (ReqDesc: contiguous planes, or the pool base for a paged cache).  The page
+// numbers of a paged cache travel in the kernel arguments, a window of KV_PAGE_WINDOW blocks per launch starting at
+// block `block0`; tokens [t0, t0 + n) are handled, t0 a multiple of 64 inside the window.
+constexpr int KV_PAGE_WINDOW = 256;
+struct KVPageWindow {
+    int page[KV_PAGE_WINDOW];
+};
+
 template <int D>
-__global__ __launch_bounds__(256) void kv_export_kernel(const bf16* __restrict__ kcache, const bf16* __restrict__ vtcache,
-                                                        bf16* __restrict__ k_out, bf16* __restrict__ v_out,
-                                                        int n, int Hkv, int cap) {
+RS_DEVICE bf16* kv_window_tile(const ReqDesc& rq, const KVPageWindow& win, int block0, bool v, int c, int block) {
+    constexpr size_t TILE = (size_t)64 * D;  // elements
+    if (rq.pages == nullptr)   // (any non-null value marks a paged cache here; the numbers come from the window)
+        return (v ? rq.vtcache : rq.kcache) + ((size_t)c * (size_t)(rq.cap >> 6) + (size_t)block) * TILE;
+    return rq.kcache + ((size_t)win.page[block - block0] * 2 * rq.hkv + (size_t)(v ? rq.hkv : 0) + (size_t)c) * TILE;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_export_kernel(ReqDesc rq, KVPageWindow win, int block0, bf16* __restrict__ k_out,
+                                                        bf16* __restrict__ v_out, int t0, int n) {
+    const int Hkv = rq.hkv;
     const size_t total = (size_t)n * Hkv * D;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int dd = (int)(i % D);
         const int c = (int)((i / D) % Hkv);
-        const int t = (int)(i / ((size_t)D * Hkv));
-        k_out[i] = kcache[((size_t)c * cap + t) * D + dd];
-        v_out[i] = vtcache[(((size_t)c * (cap / 64) + (t >> 6)) * D + dd) * 64 + (t & 63)];
+        const int t = t0 + (int)(i / ((size_t)D * Hkv));
+        const size_t o = (size_t)t0 * Hkv * D + i;
+        k_out[o] = kv_window_tile<D>(rq, win, block0, false, c, t >> 6)[(size_t)(t & 63) * D + dd];
+        v_out[o] = kv_window_tile<D>(rq, win, block0, true, c, t >> 6)[(size_t)dd * 64 + (t & 63)];
     }
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void kv_import_kernel(bf16* __restrict__ kcache, bf16* __restrict__ vtcache,
-                                                        const bf16* __restrict__ k_in, const bf16* __restrict__ v_in,
-                                                        int n, int Hkv, int cap) {
-    const int n_pad = (n + 63) & ~63;  // the last touched V block is zero-filled beyond n
+__global__ __launch_bounds__(256) void kv_import_kernel(ReqDesc rq, KVPageWindow win, int block0, const bf16* __restrict__ k_in,
+                                                        const bf16* __restrict__ v_in, int t0, int n) {
+    const int Hkv = rq.hkv;
+    const int n_pad = (n + 63) & ~63;  // the last touched V block is zero-filled beyond t0 + n
     const size_t total = (size_t)n_pad * Hkv * D;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int dd = (int)(i % D);
         const int c = (int)((i / D) % Hkv);
-        const int t = (int)(i / ((size_t)D * Hkv));
-        const bool live = t < n;
-        if (live) kcache[((size_t)c * cap + t) * D + dd] = k_in[i];
-        vtcache[(((size_t)c * (cap / 64) + (t >> 6)) * D + dd) * 64 + (t & 63)] = live ? v_in[i] : f32_to_bf16(0.0f);
+        const int tl = (int)(i / ((size_t)D * Hkv));
+        const int t = t0 + tl;
+        const bool live = tl < n;
+        const size_t o = (size_t)t0 * Hkv * D + i;
+        if (live) kv_window_tile<D>(rq, win, block0, false, c, t >> 6)[(size_t)(t & 63) * D + dd] = k_in[o];
+        kv_window_tile<D>(rq, win, block0, true, c, t >> 6)[(size_t)dd * 64 + (t & 63)] = live ? v_in[o] : f32_to_bf16(0.0f);
     }
 }

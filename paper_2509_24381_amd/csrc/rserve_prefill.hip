@@ -84,22 +84,67 @@ struct rs_ctx {
     std::vector<hipEvent_t> prof_events;  // (start, stop) pairs
 };
 
+// A pool of fixed-size pages in caller-owned device memory.  A page holds 64 tokens of ONE layer: the K tiles [64][d] of
+// all KV heads followed by their V^T tiles [d][64].  The free list lives on the host.
+struct rs_kv_pool {
+    rs_ctx* ctx;
+    char* base;
+    size_t page_bytes;
+    int n_pages;
+    int n_caches = 0;              // paged caches alive on this pool
+    std::vector<int> free_pages;   // stack: the back is handed out next
+};
+
 struct rs_kv {
     rs_ctx* ctx;
     int n_layers;
-    int cap;  // multiple of 64
+    int cap;  // contiguous: capacity in tokens, multiple of 64; paged: unused (see capacity())
     char* base;
     size_t k_bytes;      // one layer's K
     size_t layer_bytes;  // K + V^T
     std::vector<int> len;
+    rs_kv_pool* pool = nullptr;             // paged caches only
+    std::vector<std::vector<int>> pages;    // paged: pages[layer][block]
+    bool paged() const { return pool != nullptr; }
     bf16* k_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes); }
     bf16* vt_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes + k_bytes); }
+    // new pages layer `layer` needs before it can hold n_tokens
+    int pages_missing(int layer, long n_tokens) const {
+        return paged() ? std::max<long>(0, (n_tokens + 63) / 64 - (long)pages[layer].size()) : 0;
+    }
+    void take_pages(int layer, long n_tokens) {  // the caller has checked that the pool has enough
+        for (int k = pages_missing(layer, n_tokens); k > 0; --k) {
+            pages[layer].push_back(pool->free_pages.back());
+            pool->free_pages.pop_back();
+        }
+    }
+    void give_back_pages(int layer, long n_tokens) {  // keeps the pages that hold the first n_tokens
+        const size_t keep = (size_t)((n_tokens + 63) / 64);
+        while (pages[layer].size() > keep) {
+            pool->free_pages.push_back(pages[layer].back());
+            pages[layer].pop_back();
+        }
+    }
+    // the cache of `layer` as the kernels see it (row0 / T / P left to the caller; `pages` is a device pointer or a marker)
+    ReqDesc view(int layer, const int* dev_pages) const {
+        ReqDesc d{};
+        d.cap = cap;
+        d.hkv = ctx->cfg.n_kv_heads;
+        if (paged()) {
+            d.kcache = reinterpret_cast<bf16*>(pool->base);
+            d.pages = dev_pages;
+        } else {
+            d.kcache = k_of(layer);
+            d.vtcache = vt_of(layer);
+        }
+        return d;
+    }
 };
 
 namespace {
 
 struct DescSizes {
-    size_t reqs, items, vblocks, rowpos, total;
+    size_t reqs, items, vblocks, rowpos, pagetab, total;
 };
 
 DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
@@ -110,7 +155,9 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     d.items = align_up(sizeof(AttnItem) * n_items, 256);
     d.vblocks = align_up(sizeof(KVBlockItem) * n_vb, 256);
     d.rowpos = align_up(3 * sizeof(int) * (size_t)std::max(max_tokens, 1), 256);  // (temporal, height, width) per row
-    d.total = d.reqs + d.items + d.vblocks + d.rowpos;
+    // block -> page numbers of the paged caches in the call: at most max_pos / 64 + 1 blocks per request
+    d.pagetab = align_up(sizeof(int) * (size_t)std::max(max_requests, 1) * ((size_t)c->cfg.max_pos / 64 + 2), 256);
+    d.total = d.reqs + d.items + d.vblocks + d.rowpos + d.pagetab;
     return d;
 }
 
@@ -243,7 +290,7 @@ struct StepTimer {
 
 template <int D>
 rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs,
-                                const AttnItem* d_items, int n_items, const KVBlockItem* d_vb, int n_vb,
+                                const AttnItem* d_items, int n_items, const KVBlockItem* d_vb, int n_vb, bool any_paged,
                                 hipStream_t st, const StepTimer& tm) {
     const rs_layer_cfg& f = c->cfg;
     tm.begin(RS_STEP_APPEND_KV);
@@ -256,8 +303,11 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     if (c->attn_variant == 2)
         hipLaunchKernelGGL(attn_prefill_wide_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+    else if (c->attn_variant == 1 && any_paged)
+        hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, true>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     else if (c->attn_variant == 1)
-        hipLaunchKernelGGL(attn_prefill_pipelined_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
+        hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, false>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     else
         hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
@@ -268,8 +318,46 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
 }
 
 // Every check of one layer's call; changes nothing.  *total_out receives the number of rows.
+// Runs the export or import kernel over tokens [0, n): in one launch for a contiguous cache, in windows of
+// KV_PAGE_WINDOW blocks (whose page numbers ride in the kernel arguments) for a paged one.
+template <class Launch>
+rs_status for_each_kv_window(const rs_kv* kv, int layer, int n, Launch&& launch) {
+    KVPageWindow win{};
+    if (!kv->paged()) {
+        launch(kv->view(layer, nullptr), win, 0, 0, n);
+        return RS_OK;
+    }
+    const int window_tokens = KV_PAGE_WINDOW * 64;
+    for (int t0 = 0; t0 < n; t0 += window_tokens) {
+        const int nt = std::min(window_tokens, n - t0);
+        const int b0 = t0 / 64, nb = (nt + 63) / 64;
+        for (int b = 0; b < nb; ++b) win.page[b] = kv->pages[layer][b0 + b];
+        launch(kv->view(layer, reinterpret_cast<const int*>(kv->pool->base)), win, b0, t0, nt);  // non-null marker: paged
+    }
+    return RS_OK;
+}
+
+// pages a call would take from each pool
+typedef std::vector<std::pair<rs_kv_pool*, long>> PoolNeed;
+void add_need(PoolNeed& need, rs_kv_pool* pool, long n) {
+    if (n <= 0) return;
+    for (auto& e : need)
+        if (e.first == pool) {
+            e.second += n;
+            return;
+        }
+    need.emplace_back(pool, n);
+}
+rs_status check_need(const PoolNeed& need) {
+    for (const auto& e : need)
+        if (e.second > (long)e.first->free_pages.size())
+            return fail(RS_ECAPACITY, "the call needs %ld new KV pages, the pool has %zu free", e.second, e.first->free_pages.size());
+    return RS_OK;
+}
+
 rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R,
-                        const void* x, void* y, void* ws, size_t ws_bytes, int* total_out, const int* positions3 = nullptr) {
+                        const void* x, void* y, void* ws, size_t ws_bytes, int* total_out, const int* positions3 = nullptr,
+                        PoolNeed* pages_needed = nullptr) {
     if (!ctx) return fail(RS_EINVAL, "ctx is null");
     if (!w) return fail(RS_EINVAL, "weights are null");
     const rs_layer_cfg& f = ctx->cfg;
@@ -297,9 +385,19 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
     }
     for (int i = 0; i < R; ++i) {
         const long after = (long)kvs[i]->len[layer] + lens[i];
-        if (after > kvs[i]->cap)
+        if (!kvs[i]->paged() && after > kvs[i]->cap)
             return fail(RS_ECAPACITY, "request %d: %ld tokens exceed cache capacity %d", i, after, kvs[i]->cap);
         if (after > f.max_pos) return fail(RS_ECAPACITY, "request %d: %ld tokens exceed max_pos %d", i, after, f.max_pos);
+    }
+    if (pages_needed) {  // the caller adds up several layers; one layer's call checks its own need here
+        for (int i = 0; i < R; ++i)
+            if (kvs[i]->paged()) add_need(*pages_needed, kvs[i]->pool, kvs[i]->pages_missing(layer, (long)kvs[i]->len[layer] + lens[i]));
+    } else {
+        PoolNeed need;
+        for (int i = 0; i < R; ++i)
+            if (kvs[i]->paged()) add_need(need, kvs[i]->pool, kvs[i]->pages_missing(layer, (long)kvs[i]->len[layer] + lens[i]));
+        const rs_status ps = check_need(need);
+        if (ps != RS_OK) return ps;
     }
     *total_out = (int)total;
     if (total == 0) return RS_OK;
@@ -314,7 +412,8 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
     if (!aligned(ws, 256)) return fail(RS_EINVAL, "workspace must be 256-byte aligned");
     const WorkspaceLayout L = ws_layout(ctx, T, R);
     if (ws_bytes < L.total) return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, L.total);
-    if (!ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
+    // (a caller that adds up the page need of several layers reports that shortage before the missing device)
+    if (!pages_needed && !ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
     return RS_OK;
 }
 
@@ -329,7 +428,11 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     std::vector<AttnItem> items;
     std::vector<KVBlockItem> vbs;
     std::vector<int> rowpos;
+    std::vector<int> pagetab;
     rowpos.reserve(3 * (size_t)T);
+    const DescSizes ds = desc_sizes(ctx, T, R);
+    char* wsb = reinterpret_cast<char*>(ws);
+    const int* d_pagetab = reinterpret_cast<const int*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks + ds.rowpos);
     const int g = ctx->group;
     int row0 = 0;
     for (int i = 0; i < R; ++i) {
@@ -337,10 +440,10 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         if (Ti == 0) continue;
         rs_kv* kv = kvs[i];
         const int P = kv->len[layer];
-        ReqDesc d;
-        d.row0 = row0; d.T = Ti; d.P = P; d.cap = kv->cap;
-        d.kcache = kv->k_of(layer);
-        d.vtcache = kv->vt_of(layer);
+        kv->take_pages(layer, (long)P + Ti);   // (paged caches; prefill_check has made sure the pool has them)
+        ReqDesc d = kv->view(layer, d_pagetab + pagetab.size());
+        d.row0 = row0; d.T = Ti; d.P = P;
+        if (kv->paged()) pagetab.insert(pagetab.end(), kv->pages[layer].begin(), kv->pages[layer].end());
         const int ri = (int)reqs.size();
         reqs.push_back(d);
         const int item_rows = ctx->attn_variant == 2 ? ATT_WIDE_ROWS : ATT_ROWS;
@@ -358,9 +461,9 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     // heaviest work first: the tail of the launch is then made of short items
     std::stable_sort(items.begin(), items.end(), [](const AttnItem& a, const AttnItem& b) { return a.nkb > b.nkb; });
 
-    const DescSizes ds = desc_sizes(ctx, T, R);
     if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
-        sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos || ds.total > ctx->slot_bytes)
+        sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos ||
+        sizeof(int) * pagetab.size() > ds.pagetab || ds.total > ctx->slot_bytes)
         return fail(RS_EINVAL, "internal: descriptor sizing");
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -371,7 +474,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     memcpy(stage + ds.reqs, items.data(), sizeof(AttnItem) * items.size());
     memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(KVBlockItem) * vbs.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks, rowpos.data(), sizeof(int) * rowpos.size());
-    char* wsb = reinterpret_cast<char*>(ws);
+    memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos, pagetab.data(), sizeof(int) * pagetab.size());
     // (the first kernel below copies the staged descriptors into the workspace; the slot is free again once it has run)
     const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
     const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
@@ -420,9 +523,9 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     tm.end(RS_STEP_QKV_GEMM);
     // cache append, attention
     if (f.head_dim == 128)
-        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), st, tm);
+        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(), st, tm);
     else
-        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), st, tm);
+        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(), st, tm);
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
@@ -540,8 +643,10 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
     // (the pipelined attention kernel keeps its LDS in static arrays; these references make the launch stubs exist)
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
@@ -647,18 +752,87 @@ rs_status rs_kv_alloc(rs_ctx* c, int n_layers, int capacity_tokens, void* dev_me
     return RS_OK;
 }
 
-void rs_kv_free(rs_kv* kv) { delete kv; }
+size_t rs_kv_page_bytes(const rs_ctx* c) {
+    if (!c) return 0;
+    return (size_t)2 * c->cfg.n_kv_heads * 64 * c->cfg.head_dim * 2;
+}
+
+rs_status rs_kv_pool_create(rs_ctx* c, void* dev_mem, size_t bytes, rs_kv_pool** out) {
+    if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
+    *out = nullptr;
+    if (!dev_mem || !aligned(dev_mem, 256)) return fail(RS_EINVAL, "dev_mem must be a 256-byte aligned device pointer");
+    const size_t pb = rs_kv_page_bytes(c);
+    const size_t n = bytes / pb;
+    if (n == 0) return fail(RS_EWORKSPACE, "the pool's memory (%zu bytes) is smaller than one page (%zu bytes)", bytes, pb);
+    if (n > (size_t)0x7fffffff) return fail(RS_EINVAL, "more than 2^31 - 1 pages");
+    rs_kv_pool* p = new rs_kv_pool();
+    p->ctx = c;
+    p->base = reinterpret_cast<char*>(dev_mem);
+    p->page_bytes = pb;
+    p->n_pages = (int)n;
+    p->free_pages.resize(n);
+    for (size_t i = 0; i < n; ++i) p->free_pages[i] = (int)(n - 1 - i);  // page 0 is handed out first
+    *out = p;
+    return RS_OK;
+}
+
+rs_status rs_kv_pool_destroy(rs_kv_pool* p) {
+    if (!p) return RS_OK;
+    if (p->n_caches != 0) return fail(RS_ESTATE, "%d caches still use this pool", p->n_caches);
+    delete p;
+    return RS_OK;
+}
+
+int rs_kv_pool_pages(const rs_kv_pool* p) { return p ? p->n_pages : -1; }
+int rs_kv_pool_free_pages(const rs_kv_pool* p) { return p ? (int)p->free_pages.size() : -1; }
+
+rs_status rs_kv_alloc_paged(rs_ctx* c, rs_kv_pool* pool, int n_layers, rs_kv** out) {
+    if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
+    *out = nullptr;
+    if (!pool) return fail(RS_EINVAL, "pool is null");
+    if (pool->ctx != c) return fail(RS_ESTATE, "the pool belongs to another context");
+    if (n_layers <= 0) return fail(RS_EINVAL, "n_layers must be positive");
+    rs_kv* kv = new rs_kv();
+    kv->ctx = c;
+    kv->n_layers = n_layers;
+    kv->cap = 0;
+    kv->base = nullptr;
+    kv->k_bytes = kv->layer_bytes = 0;
+    kv->len.assign(n_layers, 0);
+    kv->pool = pool;
+    kv->pages.assign(n_layers, std::vector<int>());
+    ++pool->n_caches;
+    *out = kv;
+    return RS_OK;
+}
+
+void rs_kv_free(rs_kv* kv) {
+    if (!kv) return;
+    if (kv->paged()) {
+        for (int l = 0; l < kv->n_layers; ++l) kv->give_back_pages(l, 0);
+        --kv->pool->n_caches;
+    }
+    delete kv;
+}
 
 int rs_kv_len(const rs_kv* kv, int layer) {
     if (!kv || layer < 0 || layer >= kv->n_layers) return -1;
     return kv->len[layer];
 }
 
-int rs_kv_capacity(const rs_kv* kv) { return kv ? kv->cap : -1; }
+int rs_kv_capacity(const rs_kv* kv) {
+    if (!kv) return -1;
+    if (!kv->paged()) return kv->cap;
+    size_t fewest = kv->pages[0].size();
+    for (const auto& pl : kv->pages) fewest = std::min(fewest, pl.size());
+    return (int)(fewest * 64);
+}
 
 rs_status rs_kv_reset(rs_kv* kv) {
     if (!kv) return fail(RS_EINVAL, "kv is null");
     std::fill(kv->len.begin(), kv->len.end(), 0);
+    if (kv->paged())
+        for (int l = 0; l < kv->n_layers; ++l) kv->give_back_pages(l, 0);
     return RS_OK;
 }
 
@@ -667,6 +841,7 @@ rs_status rs_kv_truncate(rs_kv* kv, int layer, int n_tokens) {
     if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
     if (n_tokens < 0 || n_tokens > kv->len[layer]) return fail(RS_EINVAL, "n_tokens = %d outside [0, %d]", n_tokens, kv->len[layer]);
     kv->len[layer] = n_tokens;
+    if (kv->paged()) kv->give_back_pages(layer, n_tokens);
     return RS_OK;
 }
 
@@ -679,14 +854,15 @@ rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out, void* v_out, voi
     if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
     const rs_layer_cfg& f = kv->ctx->cfg;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const size_t total = (size_t)n * kv->ctx->kv_dim;
-    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-    if (f.head_dim == 128)
-        hipLaunchKernelGGL(kv_export_kernel<128>, dim3(blocks), dim3(256), 0, st, (const bf16*)kv->k_of(layer), (const bf16*)kv->vt_of(layer),
-                           (bf16*)k_out, (bf16*)v_out, n, f.n_kv_heads, kv->cap);
-    else
-        hipLaunchKernelGGL(kv_export_kernel<64>, dim3(blocks), dim3(256), 0, st, (const bf16*)kv->k_of(layer), (const bf16*)kv->vt_of(layer),
-                           (bf16*)k_out, (bf16*)v_out, n, f.n_kv_heads, kv->cap);
+    const int kv_dim = kv->ctx->kv_dim;
+    for_each_kv_window(kv, layer, n, [&](const ReqDesc& rq, const KVPageWindow& win, int b0, int t0, int nt) {
+        const size_t total = (size_t)nt * kv_dim;
+        const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+        if (f.head_dim == 128)
+            hipLaunchKernelGGL(kv_export_kernel<128>, dim3(blocks), dim3(256), 0, st, rq, win, b0, (bf16*)k_out, (bf16*)v_out, t0, nt);
+        else
+            hipLaunchKernelGGL(kv_export_kernel<64>, dim3(blocks), dim3(256), 0, st, rq, win, b0, (bf16*)k_out, (bf16*)v_out, t0, nt);
+    });
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -695,24 +871,33 @@ rs_status rs_kv_import(rs_kv* kv, int layer, const void* k, const void* v, int n
     if (!kv) return fail(RS_EINVAL, "kv is null");
     if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
     if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
-    if (n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
+    if (!kv->paged() && n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
     if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
+    if (kv->paged() && kv->pages_missing(layer, n_tokens) > (int)kv->pool->free_pages.size())
+        return fail(RS_ECAPACITY, "the import needs %d new KV pages, the pool has %zu free", kv->pages_missing(layer, n_tokens),
+                    kv->pool->free_pages.size());
     if (n_tokens == 0) {
         kv->len[layer] = 0;
+        if (kv->paged()) kv->give_back_pages(layer, 0);
         return RS_OK;
     }
     if (!k || !v) return fail(RS_EINVAL, "k / v is null");
     if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
     const rs_layer_cfg& f = kv->ctx->cfg;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const size_t total = align_up((size_t)n_tokens, 64) * kv->ctx->kv_dim;
-    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-    if (f.head_dim == 128)
-        hipLaunchKernelGGL(kv_import_kernel<128>, dim3(blocks), dim3(256), 0, st, kv->k_of(layer), kv->vt_of(layer), (const bf16*)k,
-                           (const bf16*)v, n_tokens, f.n_kv_heads, kv->cap);
-    else
-        hipLaunchKernelGGL(kv_import_kernel<64>, dim3(blocks), dim3(256), 0, st, kv->k_of(layer), kv->vt_of(layer), (const bf16*)k,
-                           (const bf16*)v, n_tokens, f.n_kv_heads, kv->cap);
+    const int kv_dim = kv->ctx->kv_dim;
+    if (kv->paged()) {
+        kv->take_pages(layer, n_tokens);
+        kv->give_back_pages(layer, n_tokens);
+    }
+    for_each_kv_window(kv, layer, n_tokens, [&](const ReqDesc& rq, const KVPageWindow& win, int b0, int t0, int nt) {
+        const size_t total = align_up((size_t)nt, 64) * kv_dim;
+        const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+        if (f.head_dim == 128)
+            hipLaunchKernelGGL(kv_import_kernel<128>, dim3(blocks), dim3(256), 0, st, rq, win, b0, (const bf16*)k, (const bf16*)v, t0, nt);
+        else
+            hipLaunchKernelGGL(kv_import_kernel<64>, dim3(blocks), dim3(256), 0, st, rq, win, b0, (const bf16*)k, (const bf16*)v, t0, nt);
+    });
     RS_HIP(hipGetLastError());
     kv->len[layer] = n_tokens;
     return RS_OK;
@@ -800,10 +985,17 @@ rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_lay
     if (!packed_layers) return fail(RS_EINVAL, "packed_layers is null");
     if (n_layers <= 0) return fail(RS_EINVAL, "n_layers = %d must be positive", n_layers);
     int T = 0;
+    PoolNeed need;
     for (int l = 0; l < n_layers; ++l) {  // all checks first: a failing call leaves every cache untouched
-        const rs_status s = prefill_check(ctx, &packed_layers[l], l, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, &T);
+        const rs_status s = prefill_check(ctx, &packed_layers[l], l, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, &T,
+                                          nullptr, &need);
         if (s != RS_OK) return s;
     }
+    {
+        const rs_status s = check_need(need);  // paged caches: the pages of all layers together must be there
+        if (s != RS_OK) return s;
+    }
+    if (T > 0 && !ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
     if (T == 0) return RS_OK;
     for (int l = 0; l < n_layers; ++l) {  // layer 0 reads x; later layers work on y in place
         const rs_status s = prefill_enqueue(ctx, &packed_layers[l], l, kvs, chunk_lens, R, T, l == 0 ? x : y, y, workspace, stream);

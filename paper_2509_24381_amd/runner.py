@@ -9,7 +9,7 @@ from typing import List, Sequence, Tuple
 
 import numpy as np
 
-from .binding import Context, KVCache, LayerConfig, PackedWeights
+from .binding import KVPool, Context, KVCache, LayerConfig, PackedWeights
 
 
 def to_device_bf16(a: np.ndarray):
@@ -60,6 +60,10 @@ class LayerStack:
 
     def new_cache(self, capacity: int) -> KVCache:
         return self.ctx.kv_alloc(self.n_layers, capacity)
+
+    def new_pool(self, n_pages: int) -> KVPool:
+        """A pool of KV pages (64 tokens of one layer each); `pool.new_cache(stack.n_layers)` gives growable caches."""
+        return KVPool(self.ctx, n_pages)
 
     def prefill_prompt(self, x_dev, chunks: Sequence[Tuple[int, int]], kv: KVCache, keep_layer_outputs: bool = False):
         """Runs one request's prompt chunk by chunk through all layers.

@@ -168,6 +168,86 @@ def test_prefill_argument_checks_happen_before_any_launch(lib):
     assert kv.length(0) == 0
 
 
+def make_pool(lib, ctx, n_pages, addr=0x700000000000):
+    h = C.c_void_p()
+    st = lib.rs_kv_pool_create(ctx.handle, addr, n_pages * lib.rs_kv_page_bytes(ctx.handle), C.byref(h))
+    assert st == 0, lib.rs_last_error()
+    return h
+
+
+def make_paged_kv(lib, ctx, pool, n_layers=2):
+    h = C.c_void_p()
+    assert lib.rs_kv_alloc_paged(ctx.handle, pool, n_layers, C.byref(h)) == 0, lib.rs_last_error()
+    return binding.KVCache(ctx, h.value, None)
+
+
+def test_page_pool_bookkeeping_on_the_host(lib):
+    """A page = 64 tokens of one layer, K and V of all KV heads.  Pool and paged caches are host bookkeeping until a
+    kernel runs, so every rule about pages can be checked without a GPU."""
+    ctx = Context(tiny_cfg())
+    page = lib.rs_kv_page_bytes(ctx.handle)
+    assert page == 2 * 2 * 64 * 64 * 2          # {K, V} x 2 KV heads x 64 tokens x d = 64 x bf16
+    h = C.c_void_p()
+    assert lib.rs_kv_pool_create(ctx.handle, 0x700000000010, 10 * page, C.byref(h)) == -1   # misaligned
+    assert lib.rs_kv_pool_create(ctx.handle, None, 10 * page, C.byref(h)) == -1
+    assert lib.rs_kv_pool_create(ctx.handle, 0x700000000000, page - 1, C.byref(h)) == -3    # not even one page
+    pool = make_pool(lib, ctx, 5)
+    assert lib.rs_kv_pool_pages(pool) == 5 and lib.rs_kv_pool_free_pages(pool) == 5
+    assert lib.rs_kv_pool_pages(None) == -1 and lib.rs_kv_pool_free_pages(None) == -1
+    assert lib.rs_kv_alloc_paged(ctx.handle, None, 2, C.byref(h)) == -1
+    assert lib.rs_kv_alloc_paged(ctx.handle, pool, 0, C.byref(h)) == -1
+    stranger = Context(tiny_cfg())
+    assert lib.rs_kv_alloc_paged(stranger.handle, pool, 2, C.byref(h)) == -4                 # another context's pool
+    kv = make_paged_kv(lib, ctx, pool)
+    assert kv.capacity == 0 and kv.length(0) == 0 and lib.rs_kv_pool_free_pages(pool) == 5   # pages come with tokens
+    assert lib.rs_kv_pool_destroy(pool) == -4                                                # a cache is alive
+    w, mem = fake_weights(), FakeDeviceMemory()
+
+    class X:
+        def __init__(self, t):
+            self.shape = (t, 256)
+        def data_ptr(self):
+            return 0x7B0000000000
+
+    def status_of(fn):
+        with pytest.raises(RsError) as e:
+            fn()
+        return e.value.status_name
+
+    # 5 free pages: 128 rows of one layer need 2 pages -> passes every host check (and then misses the GPU here);
+    # a second cache asking for 4 more pages in the same call does not fit; nothing is taken by a failing call
+    kv2 = make_paged_kv(lib, ctx, pool)
+    st = status_of(lambda: ctx.prefill_batch(w, 0, [kv, kv2], [64, 64], X(128), X(128), mem))
+    assert st in ("RS_EHIP",)   # enough pages: the call got as far as needing a device
+    small = Context(tiny_cfg(max_tokens_per_call=512, max_requests=4))
+    pool_s = make_pool(lib, small, 5, addr=0x6F0000000000)
+    a, b = make_paged_kv(lib, small, pool_s), make_paged_kv(lib, small, pool_s)
+    big = FakeDeviceMemory()
+    assert status_of(lambda: small.prefill_batch(w, 0, [a, b], [129, 200], X(329), X(329), big)) == "RS_ECAPACITY"   # 3 + 4 pages
+    assert lib.rs_kv_pool_free_pages(pool_s) == 5 and a.length(0) == 0 and a.capacity == 0
+    # all layers in one call: 2 layers x 3 pages = 6 > 5, although either layer alone would fit
+    assert status_of(lambda: small.prefill_model_batch([w, w], [a], [129], X(129), X(129), big)) == "RS_ECAPACITY"
+    assert lib.rs_kv_pool_free_pages(pool_s) == 5
+    # the position limit still holds for a cache without a fixed capacity (max_pos = 512 here)
+    roomy = make_pool(lib, small, 64, addr=0x6E0000000000)
+    c = make_paged_kv(lib, small, roomy)
+    assert status_of(lambda: small.prefill_batch(w, 0, [c], [512], X(512), X(512), big)) == "RS_EHIP"       # fits: needs the GPU
+    assert lib.rs_kv_import(c.handle, 0, 0x7B0000000000, 0x7B0000100000, 513, None) == -2                   # beyond max_pos
+    lib.rs_kv_free(c.handle)
+    c.handle = None
+    assert lib.rs_kv_pool_destroy(roomy) == 0
+    # import: page need is checked before anything else is touched
+    assert lib.rs_kv_import(a.handle, 0, 0x7B0000000000, 0x7B0000100000, 64 * 6, None) == -2   # RS_ECAPACITY: 6 pages
+    assert lib.rs_kv_import(a.handle, 0, None, None, 0, None) == 0
+    assert lib.rs_kv_pool_free_pages(pool_s) == 5
+    # freeing the caches lets the pools go
+    for c in (kv, kv2, a, b):
+        lib.rs_kv_free(c.handle)
+        c.handle = None
+    assert lib.rs_kv_pool_destroy(pool) == 0 and lib.rs_kv_pool_destroy(pool_s) == 0
+    assert lib.rs_kv_pool_destroy(None) == 0
+
+
 def test_valid_call_without_a_gpu_fails_loudly(lib):
     """On a host without a GPU a call that passes every check must return RS_EHIP, never pretend to have run."""
     import torch
