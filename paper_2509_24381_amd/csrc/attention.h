@@ -84,15 +84,33 @@ RS_DEVICE KVHeadTiles kv_head_tiles(const ReqDesc& rq, int kvh) {
     return t;
 }
 
+constexpr int ATT_ROWS = 128;  // stacked query rows per workgroup
+constexpr int ATT_KEYS = 64;   // keys per tile
+
 struct AttnItem {
     int req;
     int kvh;
     int qblock;  // block of stacked query rows (128, or 256 for the wide kernel)
-    int nkb;     // number of 64-key tiles this block must visit
+    int nkb;     // number of 64-key tiles this block must visit (tiles [0, nkb), or [kb0, nkb) for a part of a split block)
+    int kb0;     // first tile of this part (0 unless the block's key range is split)
+    int slot;    // -1: the workgroup finishes the block and writes the output; >= 0: it leaves an unnormalised partial
+                 // result in this slot of the split buffer (see AttnPartial) for attn_merge_kernel
+    int pad0_, pad1_;
 };
 
-constexpr int ATT_ROWS = 128;  // stacked query rows per workgroup
-constexpr int ATT_KEYS = 64;   // keys per tile
+// Split key ranges.  With few query rows and a long cache there are fewer blocks than compute units (a 256-token chunk
+// at the 7B shape gives 56), each walking the whole cache.  The host then cuts a block's tiles into up to 8 consecutive
+// parts, one workgroup each; a part leaves  O~ = sum_k 2^((s_k - m) c) v_k  (fp32, unnormalised), its reference maximum m
+// and its row sums l in a slot of the split buffer, and attn_merge_kernel combines the parts of a block:
+//   M = max_p m_p,  w_p = 2^((m_p - M) c),  out = sum_p w_p O~_p / sum_p w_p l_p.
+// A slot holds 128 rows: O~ as [D/4 chunks of 4 floats][128 rows] (the 32 lanes of a store cover 512 contiguous bytes),
+// then m[128], then l[128].
+template <int D>
+struct AttnPartial {
+    static constexpr int CHUNKS = D / 4;
+    static constexpr size_t SLOT_FLOATS = (size_t)ATT_ROWS * (D + 2);
+};
+
 // The software-pipelined kernels keep a query's reference maximum until a tile's maximum exceeds it by more than this
 // many powers of two (in the exponent's units, i.e. after the 1/sqrt(d) log2 e scaling): probabilities then reach at most
 // 2^8 instead of 1, which fp32 sums and bf16's relative rounding do not mind, and the final division by the row sum
@@ -317,7 +335,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
                                                                         const AttnItem* __restrict__ items,
                                                                         const bf16* __restrict__ qkv, int ld_qkv,
                                                                         bf16* __restrict__ out, int ld_out,
-                                                                        int g, float scale_log2e) {
+                                                                        int g, float scale_log2e,
+                                                                        float* __restrict__ split_buf) {
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
     constexpr int K_ROW_BYTES = D * 2;
@@ -452,13 +471,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     };
 
     // ---- prologue: K(0), V(0), K(1) into LDS; scores and maximum of tile 0
-    int pg_v = page_of(1);   // page of block kb + 1 (V is fetched one tile behind K)
-    int pg_k = page_of(2);   // page of block kb + 2
+    const int kb0 = item.kb0;       // this workgroup's tiles are [kb0, nkb)
+    int pg_v = page_of(kb0 + 1);   // page of block kb + 1 (V is fetched one tile behind K)
+    int pg_k = page_of(kb0 + 2);   // page of block kb + 2
     {
-        const int pg0 = page_of(0);
-        fetch_k(k_buf0, 0, pg0);
-        fetch_v(v_buf0, 0, pg0);
-        fetch_k(k_buf1, 1, pg_v);
+        const int pg0 = page_of(kb0);
+        fetch_k(k_buf0, kb0, pg0);
+        fetch_v(v_buf0, kb0, pg0);
+        fetch_k(k_buf1, kb0 + 1, pg_v);
     }
     __syncthreads();
     f32x16 sA[2], sB[2];
@@ -467,8 +487,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     for (int kk = 0; kk < KSTEPS; ++kk)
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) score_mfma(sA, k_buf0, kk, mi);
-    tile_max(sA, 0);
-    __syncthreads();  // every wavefront is done with K(0): iteration 0 may overwrite it
+    tile_max(sA, kb0 * ATT_KEYS);
+    __syncthreads();  // every wavefront is done with the first K tile: the first iteration may overwrite it
 
     // one iteration: scur = raw scores of tile kb (masked, maximum known); snext receives those of tile kb+1.
     // k_next holds K(kb+1), v_cur V(kb); k_fill (= K(kb)'s buffer) receives K(kb+2), v_fill (= V(kb-1)'s) V(kb+1).
@@ -568,7 +588,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
         __syncthreads();
     };
 
-    int kb = 0;
+    int kb = kb0;
     for (; kb + 1 < nkb; kb += 2) {
         iteration(kb, sA, sB, k_buf1, k_buf0, v_buf0, v_buf1);
         iteration(kb + 1, sB, sA, k_buf0, k_buf1, v_buf1, v_buf0);
@@ -576,6 +596,25 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     if (kb < nkb) iteration(kb, sA, sB, k_buf1, k_buf0, v_buf0, v_buf1);
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
+    if (item.slot >= 0) {
+        // a part of a split block: unnormalised output, reference maximum and row sum go to the slot (all 128 rows of the
+        // block, clamped duplicates included: the merge kernel decides what is stored)
+        float* const slot = split_buf + (size_t)item.slot * AttnPartial<D>::SLOT_FLOATS;
+        const int rs = wave * 32 + l32;  // row inside the block
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 o = {acc_o[t][4 * q], acc_o[t][4 * q + 1], acc_o[t][4 * q + 2], acc_o[t][4 * q + 3]};
+                // chunk (features 32t + 8q + 4half .. +3) of row rs
+                *reinterpret_cast<f32x4*>(slot + ((size_t)(t * 8 + q * 2 + half) * ATT_ROWS + rs) * 4) = o;
+            }
+        if (half == 0) {
+            slot[(size_t)D * ATT_ROWS + rs] = m_run;
+            slot[(size_t)(D + 1) * ATT_ROWS + rs] = l_tot;
+        }
+        return;
+    }
     if (row < rows_total) {
         const float inv = 1.0f / l_tot;
         const uint32_t m = (uint32_t)(rq.row0 + tok);
@@ -593,16 +632,63 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     }
 }
 
-// ------------------------------------------------------------------------------------------------------------------
-// Wide variant: 256 stacked query rows per workgroup, each wavefront holding TWO tiles of 32 queries, one wavefront per
-// SIMD (up to 512 registers).  Every K / V fragment read from LDS now feeds two MFMAs; with one query tile per wavefront
-// the kernel above needs 1 KB of LDS reads per MFMA, which at two workgroups per compute unit is the LDS port's whole
-// bandwidth (the measured time per key tile equals 256 KB / 128 B per clock).  With a single wavefront per SIMD nothing
-// but the instruction order overlaps the matrix pipe and the vector ALU, so the softmax of tile kb is cut into single
-// values (one scale-and-exponential per MFMA, conversion and row sum per pair) and laid behind the MFMAs of BOTH products:
-// 40 of the 64 values behind the 32 score MFMAs of tile kb+1, the rest behind the first three quarters of the P.V MFMAs
-// of tile kb (the P fragment of keys 16q..16q+15 is complete before the MFMAs that consume it), and the running maximum
-// of tile kb+1 behind the last quarter.
+// Combines the parts of split blocks (see AttnPartial).  One workgroup per block: thread (row, c16) handles row `row` of
+// the block and the chunks c16, c16 + 2, ... of its D/4 chunks of 4 features.
+struct AttnMergeItem {
+    int req;
+    int kvh;
+    int qblock;
+    int n_parts;
+    int slot0;  // the parts' slots are slot0 .. slot0 + n_parts - 1
+    int pad0_, pad1_, pad2_;
+};
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const ReqDesc* __restrict__ reqs, const AttnMergeItem* __restrict__ items,
+                                                         const float* __restrict__ split_buf, bf16* __restrict__ out, int ld_out,
+                                                         int g, float scale_log2e) {
+    const AttnMergeItem item = items[blockIdx.x];
+    const ReqDesc rq = reqs[item.req];
+    const int rs = threadIdx.x & (ATT_ROWS - 1), c2 = threadIdx.x >> 7;
+    const int row = item.qblock * ATT_ROWS + rs;
+    if (row >= rq.T * g) return;
+    const int tok = row / g;
+    const int head = item.kvh * g + (row - tok * g);
+    const float* const base = split_buf + (size_t)item.slot0 * AttnPartial<D>::SLOT_FLOATS;
+    float m_all = -INFINITY;
+    for (int p = 0; p < item.n_parts; ++p) m_all = fmaxf(m_all, base[p * AttnPartial<D>::SLOT_FLOATS + (size_t)D * ATT_ROWS + rs]);
+    float l_all = 0.0f;
+    float w[8];  // at most 8 parts
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        w[p] = 0.0f;
+        if (p < item.n_parts) {
+            const float* sp = base + p * AttnPartial<D>::SLOT_FLOATS;
+            w[p] = __builtin_amdgcn_exp2f((sp[(size_t)D * ATT_ROWS + rs] - m_all) * scale_log2e);
+            l_all += w[p] * sp[(size_t)(D + 1) * ATT_ROWS + rs];
+        }
+    }
+    const float inv = 1.0f / l_all;
+    const uint32_t m = (uint32_t)(rq.row0 + tok);
+    char* const op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u;
+    const int ks0 = (head * D) >> 4;
+    for (int c = c2; c < AttnPartial<D>::CHUNKS; c += 2) {
+        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            if (p < item.n_parts) {
+                const f32x4 o = *reinterpret_cast<const f32x4*>(base + p * AttnPartial<D>::SLOT_FLOATS + ((size_t)c * ATT_ROWS + rs) * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += w[p] * o[e];
+            }
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = f32_to_bf16(acc[e] * inv);
+        // chunk c = 8t + 2q + half holds features 32t + 8q + 4half .. +3: the same place the unsplit kernel writes
+        const int t = c >> 3, q = (c >> 1) & 3, hf = c & 1;
+        *reinterpret_cast<bf16x4*>(op + hf * 8 + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o4;
+    }
+}
+
 constexpr int ATT_WIDE_ROWS = 256;
 
 // v_mfma_f32_32x32x16_bf16 with its accumulator in ordinary vector registers.  In a kernel that may use more than 256

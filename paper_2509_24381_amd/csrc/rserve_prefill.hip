@@ -71,6 +71,7 @@ struct rs_ctx {
     int next_slot = 0;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
     int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
+    int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
     int attn_variant = 1;     // RS_ATTN environment variable: 2 the wide software-pipelined attention kernel (256 rows per
                               // workgroup), 1 the 128-row software-pipelined one, 0 the plain one
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
@@ -144,12 +145,19 @@ struct rs_kv {
 namespace {
 
 struct DescSizes {
-    size_t reqs, items, vblocks, rowpos, pagetab, total;
+    size_t reqs, items, vblocks, rowpos, pagetab, mitems, total;
 };
+
+constexpr int ATT_MAX_PARTS = 8;   // parts per block of a split key range
+constexpr int ATT_MIN_PART_TILES = 8;
+// slots of the split buffer: blocks are split only when there are fewer of them than compute units, into about two
+// workgroups per unit in total (sized for the 256 units of an MI355X; a block that finds no free slots stays whole)
+size_t attn_split_slots(const rs_ctx*) { return 768; }
 
 DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     DescSizes d;
-    const size_t n_items = ((size_t)(max_tokens * (size_t)c->group + ATT_ROWS - 1) / ATT_ROWS + max_requests) * c->cfg.n_kv_heads;
+    const size_t n_items = ((size_t)(max_tokens * (size_t)c->group + ATT_ROWS - 1) / ATT_ROWS + max_requests) * c->cfg.n_kv_heads +
+                           attn_split_slots(c);
     const size_t n_vb = (size_t)max_tokens / 64 + 2 * (size_t)max_requests + 1;
     d.reqs = align_up(sizeof(ReqDesc) * std::max(max_requests, 1), 256);
     d.items = align_up(sizeof(AttnItem) * n_items, 256);
@@ -157,7 +165,8 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     d.rowpos = align_up(3 * sizeof(int) * (size_t)std::max(max_tokens, 1), 256);  // (temporal, height, width) per row
     // block -> page numbers of the paged caches in the call: at most max_pos / 64 + 1 blocks per request
     d.pagetab = align_up(sizeof(int) * (size_t)std::max(max_requests, 1) * ((size_t)c->cfg.max_pos / 64 + 2), 256);
-    d.total = d.reqs + d.items + d.vblocks + d.rowpos + d.pagetab;
+    d.mitems = align_up(sizeof(AttnMergeItem) * attn_split_slots(c), 256);
+    d.total = d.reqs + d.items + d.vblocks + d.rowpos + d.pagetab + d.mitems;
     return d;
 }
 
@@ -198,7 +207,7 @@ int choose_splitk(const rs_ctx* c, int M, int units, int k_steps) {
 }
 
 struct WorkspaceLayout {
-    size_t qkv, xf, attn, r, act, partial, inv_rms1, inv_rms2, rowss, desc, total;
+    size_t qkv, xf, attn, r, act, partial, attn_split, inv_rms1, inv_rms2, rowss, desc, total;
 };
 
 WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
@@ -218,6 +227,7 @@ WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
     w.r = take(tp * f.hidden * 2);
     w.act = take(tp * f.mlp_inter * 2);
     w.partial = take(4 * t * f.hidden * 4);  // up to 4 split-K partial planes of [T, H] fp32
+    w.attn_split = take(attn_split_slots(c) * (size_t)ATT_ROWS * (f.head_dim + 2) * 4);  // partial results of split key ranges
     w.inv_rms1 = take(tp * 4);
     w.inv_rms2 = take(tp * 4);
     w.rowss = take(tp * (f.hidden / 32) * 4);
@@ -291,7 +301,7 @@ struct StepTimer {
 template <int D>
 rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs,
                                 const AttnItem* d_items, int n_items, const KVBlockItem* d_vb, int n_vb, bool any_paged,
-                                hipStream_t st, const StepTimer& tm) {
+                                float* split_buf, const AttnMergeItem* d_mitems, int n_mitems, hipStream_t st, const StepTimer& tm) {
     const rs_layer_cfg& f = c->cfg;
     tm.begin(RS_STEP_APPEND_KV);
     hipLaunchKernelGGL(append_kv_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
@@ -305,14 +315,19 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     else if (c->attn_variant == 1 && any_paged)
         hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, true>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
-                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e, split_buf);
     else if (c->attn_variant == 1)
         hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, false>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
-                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
+                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e, split_buf);
     else
         hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     RS_HIP(hipGetLastError());
+    if (n_mitems > 0) {
+        hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(n_mitems), dim3(256), 0, st, d_reqs, d_mitems, (const float*)split_buf, attn,
+                           c->q_dim, c->group, scale_log2e);
+        RS_HIP(hipGetLastError());
+    }
     tm.end(RS_STEP_ATTENTION);
     return RS_OK;
 }
@@ -451,19 +466,51 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         for (int qb = 0; qb < nqb; ++qb) {
             const int t_max = std::min(Ti - 1, (qb * item_rows + item_rows - 1) / g);
             const int nkb = (P + t_max + 1 + ATT_KEYS - 1) / ATT_KEYS;
-            for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb});
+            for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb, 0, -1, 0, 0});
         }
         for (int b = P / 64; b <= (P + Ti - 1) / 64; ++b) vbs.push_back(KVBlockItem{ri, b});
         for (int t = 0; t < Ti; ++t)
             for (int ax = 0; ax < 3; ++ax) rowpos.push_back(positions3 ? positions3[3 * (size_t)(row0 + t) + ax] : P + t);
         row0 += Ti;
     }
+    // Few blocks and long caches: cut the key ranges so that about two workgroups per compute unit exist (the default
+    // kernel only).  A part has at least ATT_MIN_PART_TILES tiles, so every row of the block sees keys in each part: the
+    // rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden from some of them.
+    std::vector<AttnMergeItem> mitems;
+    if (ctx->attn_variant == 1 && !items.empty()) {
+        const int blocks = (int)items.size();
+        int want = ctx->attn_split;
+        if (want == 0) want = blocks < ctx->n_cu ? std::min(ATT_MAX_PARTS, (2 * ctx->n_cu + blocks - 1) / blocks) : 1;
+        if (want > 1) {
+            std::vector<AttnItem> cut;
+            int slots = 0;
+            const int slot_cap = (int)attn_split_slots(ctx);
+            for (const AttnItem& it : items) {
+                const int parts = std::min(want, it.nkb / ATT_MIN_PART_TILES);
+                if (parts < 2 || slots + parts > slot_cap) {
+                    cut.push_back(it);
+                    continue;
+                }
+                mitems.push_back(AttnMergeItem{it.req, it.kvh, it.qblock, parts, slots, 0, 0, 0});
+                for (int p = 0; p < parts; ++p) {
+                    AttnItem part = it;
+                    part.kb0 = (int)((long)p * it.nkb / parts);
+                    part.nkb = (int)((long)(p + 1) * it.nkb / parts);
+                    part.slot = slots++;
+                    cut.push_back(part);
+                }
+            }
+            items.swap(cut);
+        }
+    }
     // heaviest work first: the tail of the launch is then made of short items
-    std::stable_sort(items.begin(), items.end(), [](const AttnItem& a, const AttnItem& b) { return a.nkb > b.nkb; });
+    std::stable_sort(items.begin(), items.end(),
+                     [](const AttnItem& a, const AttnItem& b) { return a.nkb - a.kb0 > b.nkb - b.kb0; });
 
     if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
         sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos ||
-        sizeof(int) * pagetab.size() > ds.pagetab || ds.total > ctx->slot_bytes)
+        sizeof(int) * pagetab.size() > ds.pagetab || sizeof(AttnMergeItem) * mitems.size() > ds.mitems ||
+        ds.total > ctx->slot_bytes)
         return fail(RS_EINVAL, "internal: descriptor sizing");
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -475,11 +522,15 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     memcpy(stage + ds.reqs + ds.items, vbs.data(), sizeof(KVBlockItem) * vbs.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks, rowpos.data(), sizeof(int) * rowpos.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos, pagetab.data(), sizeof(int) * pagetab.size());
+    memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab, mitems.data(), sizeof(AttnMergeItem) * mitems.size());
     // (the first kernel below copies the staged descriptors into the workspace; the slot is free again once it has run)
     const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
     const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
     const KVBlockItem* d_vb = reinterpret_cast<const KVBlockItem*>(wsb + L.desc + ds.reqs + ds.items);
     const int* d_rowpos = reinterpret_cast<const int*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks);
+    const AttnMergeItem* d_mitems =
+        reinterpret_cast<const AttnMergeItem*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab);
+    float* attn_split = reinterpret_cast<float*>(wsb + L.attn_split);
 
     bf16* qkv = reinterpret_cast<bf16*>(wsb + L.qkv);
     bf16* xf = reinterpret_cast<bf16*>(wsb + L.xf);
@@ -523,9 +574,11 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     tm.end(RS_STEP_QKV_GEMM);
     // cache append, attention
     if (f.head_dim == 128)
-        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(), st, tm);
+        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
+                                       attn_split, d_mitems, (int)mitems.size(), st, tm);
     else
-        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(), st, tm);
+        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
+                                      attn_split, d_mitems, (int)mitems.size(), st, tm);
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
@@ -593,6 +646,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->mrope_b0 = c->mrope_b1 = f.head_dim / 2;  // 1-D RoPE: every pair turns with the first axis
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
     if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
+    if (const char* e = getenv("RS_ATTN_SPLIT")) c->attn_split = std::max(0, std::min(atoi(e), ATT_MAX_PARTS));
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
     c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;
@@ -647,6 +701,8 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_merge_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_merge_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));

@@ -532,3 +532,27 @@ def test_workload5_72b_32768_sampled_rows():
         kind = "text" if r >= 30720 else "image"
         print(f"[parity] w5 row {r} ({kind}): rel_fro = {e:.3e}", flush=True)
         assert e <= 3e-2, f"w5 row {r}: rel_fro {e:.3e}"
+
+
+# ------------------------------------------------------------------ split key ranges (few query rows, long cache)
+@pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 3000, 70), ("small128", 2100, 33), ("small128", 1500, 300)])
+def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_new):
+    """A short chunk against a long cache gives fewer attention blocks than compute units; the library then cuts each
+    block's key range into parts and merges them.  The result must meet the oracle's bar, and agree closely with the
+    unsplit kernel (RS_ATTN_SPLIT=1 in a child process would be the same code path as large chunks take: here the two
+    are compared through the oracle)."""
+    shape = synth.TINY if shape_name == "tiny" else synth.LayerShape("small128", 256, 4, 2, 128, 512)
+    w = synth.layer_weights(shape, 61, gains="uniform")
+    rng = np.random.default_rng(62)
+    pk = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+    pv = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+    rows = synth.prompt_rows([("image", t_new // 2), ("text", t_new - t_new // 2)], shape.hidden, 63)
+    reqs = [synth.BatchRequest(prior, pk, pv, rows)]
+    y, caches = run_batch(shape, w, reqs, capacity=prior + 512)
+    y_ref, caches_ref = oracle_batch(shape, w, reqs)
+    check(f"{shape_name} split-range y (P={prior}, T={t_new})", y, y_ref)
+    w.wd = np.zeros_like(w.wd)            # and with the MLP off, so that the attention term is what is compared
+    y, _ = run_batch(shape, w, reqs, capacity=prior + 512)
+    y_ref, _ = oracle_batch(shape, w, reqs)
+    h = t_new // 2   # (text rows only: on image rows the bf16 rounding of y is as large as the attention term itself)
+    check(f"{shape_name} split-range attention term", (y - rows)[h:], (y_ref - rows)[h:], tol=2e-2)
