@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     auto stream_advance = [&]() {
         d_slot = (d_slot + GS_SLOT_BYTES) & (GS_LDS_BYTES - 1);
         d_koff += GS_BK * 2;
-        if (++d_s == ns) {
+        if (__builtin_expect(++d_s == ns, 0)) {
             d_s = 0;
             d_koff = k0;
             ++d_tile;
@@ -458,10 +458,19 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
             phase(std::integral_constant<int, 2>{}, wa, xc, wb, aw[3] + c_slot, std::integral_constant<int, W_A>{},
                   [&](auto ec) { load_w(ec); });
             tie_wait_lgkm0<NT>(wb);
-            phase(std::integral_constant<int, 3>{}, wb, xc, wa, aw[0] + n_slot, std::integral_constant<int, W_B>{},
-                  [&](auto ec) { load_w(std::integral_constant<int, decltype(ec)::value + W_A>{}); });
-            if (d_nt > NT) load_w(std::integral_constant<int, NT < GS_MAX_NT ? NT : 0>{});  // the stream is in a wider tile
-            stream_advance();
+            // (the stream's bookkeeping - scalar work and a rarely taken branch - rides behind an MFMA in the middle of the
+            // phase like a memory instruction: left after the phase's last MFMA it holds up the next step's first one by
+            // about 150 clocks, with one wavefront per SIMD and nothing else to issue)
+            phase(std::integral_constant<int, 3>{}, wb, xc, wa, aw[0] + n_slot, std::integral_constant<int, W_B + 1>{},
+                  [&](auto ec) {
+                      if constexpr (decltype(ec)::value < W_B) {
+                          load_w(std::integral_constant<int, decltype(ec)::value + W_A>{});
+                      } else {
+                          if (__builtin_expect(d_nt > NT, 0))
+                              load_w(std::integral_constant<int, NT < GS_MAX_NT ? NT : 0>{});  // the stream is in a wider tile
+                          stream_advance();
+                      }
+                  });
             c_slot = n_slot;
         };
 
