@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # Bytes crossing the L2 / fabric boundary per gate/up GEMM launch at T=2048 on the 7B shape, from the two rocprofv3 --pmc
 # passes summarised in profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
 # factors a plain copy kernel of known size gives).  Algorithmic bytes of the same launch: 363.9e6.
-GATE_UP_TRAFFIC_BYTES = (466407.9 * 2.0 + 151296.0 * 1.0) * 1024
+GATE_UP_TRAFFIC_BYTES = (466051.5 * 2.0 + 151296.0 * 1.0) * 1024
 
 
 def cpu_baseline(wl, w0, x, target_seconds: float):

@@ -149,7 +149,8 @@ struct DescSizes {
 };
 
 constexpr int ATT_MAX_PARTS = 8;   // parts per block of a split key range
-constexpr int ATT_MIN_PART_TILES = 8;
+constexpr int ATT_MIN_PART_TILES = 16;     // a part is worth a workgroup and its share of the merge from about 1000 keys
+constexpr int ATT_MIN_SPLIT_TILES = 64;    // no block of the call is split unless the longest walks at least 4096 keys
 // slots of the split buffer: blocks are split only when there are fewer of them than compute units, into about two
 // workgroups per unit in total (sized for the 256 units of an MI355X; a block that finds no free slots stays whole)
 size_t attn_split_slots(const rs_ctx*) { return 768; }
@@ -474,13 +475,21 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         row0 += Ti;
     }
     // Few blocks and long caches: cut the key ranges so that about two workgroups per compute unit exist (the default
-    // kernel only).  A part has at least ATT_MIN_PART_TILES tiles, so every row of the block sees keys in each part: the
-    // rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden from some of them.
+    // kernel only).  A part has at least ATT_MIN_PART_TILES tiles (8 would do for what follows), so every row of the block
+    // sees keys in each part: the rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden
+    // from some of them.
     std::vector<AttnMergeItem> mitems;
     if (ctx->attn_variant == 1 && !items.empty()) {
         const int blocks = (int)items.size();
         int want = ctx->attn_split;
-        if (want == 0) want = blocks < ctx->n_cu ? std::min(ATT_MAX_PARTS, (2 * ctx->n_cu + blocks - 1) / blocks) : 1;
+        if (want == 0) {
+            // (the merge is a second kernel: about 10 us with its launch, which short key ranges do not win back - a
+            // 512-row chunk on a 2048-token prompt is faster unsplit)
+            int longest = 0;
+            for (const AttnItem& it : items) longest = std::max(longest, it.nkb);
+            want = (blocks < ctx->n_cu && longest >= ATT_MIN_SPLIT_TILES)
+                       ? std::min(ATT_MAX_PARTS, (2 * ctx->n_cu + blocks - 1) / blocks) : 1;
+        }
         if (want > 1) {
             std::vector<AttnItem> cut;
             int slots = 0;

@@ -212,7 +212,7 @@ def test_alternative_kernel_paths_meet_the_same_bar(env):
     compute-unit count: small values give wide strips, i.e. every tile width from 2 to 8 units on these small shapes,
     where the default gives one unit per strip), and the other two attention kernels (RS_ATTN 0: not software-pipelined,
     2: 256 query rows per workgroup) and a fixed number of parts per attention block (RS_ATTN_SPLIT: 1 never splits a key
-    range, 3 splits every block with at least 16 key tiles in three) are selectable by environment variable; each must pass the
+    range, 3 cuts every block with at least 48 key tiles in three and those with at least 32 in two) are selectable by environment variable; each must pass the
     workload-1 parity test on its own (run in a child process because the choice is read once per process)."""
     child_env = dict(os.environ, **env)
     proc = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", os.path.join(ROOT, "tests", "test_gpu_parity.py"),

@@ -535,7 +535,7 @@ def test_workload5_72b_32768_sampled_rows():
 
 
 # ------------------------------------------------------------------ split key ranges (few query rows, long cache)
-@pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 3000, 70), ("small128", 2100, 33), ("small128", 1500, 300)])
+@pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 4500, 70), ("small128", 4200, 33), ("small128", 5000, 300)])
 def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_new):
     """A short chunk against a long cache gives fewer attention blocks than compute units; the library then cuts each
     block's key range into parts and merges them.  The result must meet the oracle's bar, and agree closely with the
