@@ -47,6 +47,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int RING_SLOTS = 32;
+constexpr int RING_CHECKPOINT = 8;
 
 }  // namespace
 
@@ -65,10 +66,15 @@ struct rs_ctx {
     // pinned staging ring for per-call descriptors
     char* pinned[RING_SLOTS] = {};
     char* pinned_dev[RING_SLOTS] = {};  // the same buffers as the device addresses them
+    // A slot may be overwritten once the first kernel of the call that used it has run.  Recording an event behind that
+    // kernel in every call would tell, but an event record holds the stream up for about 6 us; so events are recorded only
+    // at checkpoints: after every RING_CHECKPOINT-th use, and - on the stream that is being left - whenever the caller's
+    // stream changes.  Uses are numbered; the first checkpoint at or after use u is on u's stream and behind its kernel.
     hipEvent_t slot_done[RING_SLOTS] = {};
-    bool slot_used[RING_SLOTS] = {};
+    long slot_recorded_at[RING_SLOTS];   // the use number slot_done[slot] was last recorded at (-1: never)
     size_t slot_bytes = 0;
-    int next_slot = 0;
+    long use_count = 0;                   // uses so far; use u occupies slot u % RING_SLOTS
+    hipStream_t last_stream = nullptr;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
     int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
     int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
@@ -523,8 +529,29 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         return fail(RS_EINVAL, "internal: descriptor sizing");
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const int slot = ctx->next_slot;
-    if (ctx->slot_used[slot]) RS_HIP(hipEventSynchronize(ctx->slot_done[slot]));
+    const long use = ctx->use_count;
+    const int slot = (int)(use % RING_SLOTS);
+    if (use > 0 && st != ctx->last_stream) {  // leaving a stream: a checkpoint behind its last use, unless there is one
+        const int prev = (int)((use - 1) % RING_SLOTS);
+        if (ctx->slot_recorded_at[prev] != use - 1) {
+            if (hipEventRecord(ctx->slot_done[prev], ctx->last_stream) != hipSuccess) {
+                (void)hipGetLastError();       // (the stream is gone: wait for everything instead)
+                RS_HIP(hipDeviceSynchronize());
+                RS_HIP(hipEventRecord(ctx->slot_done[prev], st));
+            }
+            ctx->slot_recorded_at[prev] = use - 1;
+        }
+    }
+    if (use >= RING_SLOTS) {  // the slot's previous use: wait for the first checkpoint at or after it
+        const long old = use - RING_SLOTS;
+        bool waited = false;
+        for (long u = old; u < old + RING_CHECKPOINT && !waited; ++u)
+            if (ctx->slot_recorded_at[u % RING_SLOTS] == u) {
+                RS_HIP(hipEventSynchronize(ctx->slot_done[u % RING_SLOTS]));
+                waited = true;
+            }
+        if (!waited) return fail(RS_EINVAL, "internal: no checkpoint behind use %ld of the descriptor ring", old);
+    }
     char* stage = ctx->pinned[slot];
     memcpy(stage, reqs.data(), sizeof(ReqDesc) * reqs.size());
     memcpy(stage + ds.reqs, items.data(), sizeof(AttnItem) * items.size());
@@ -564,9 +591,14 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
                        inv_rms1, T, H, f.rms_eps, reinterpret_cast<const uint4*>(ctx->pinned_dev[slot]),
                        reinterpret_cast<uint4*>(wsb + L.desc), desc_chunks);
     RS_HIP(hipGetLastError());
-    RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
-    ctx->slot_used[slot] = true;
-    ctx->next_slot = (slot + 1) % RING_SLOTS;
+    if (use % RING_CHECKPOINT == RING_CHECKPOINT - 1) {
+        RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
+        ctx->slot_recorded_at[slot] = use;
+    } else {
+        ctx->slot_recorded_at[slot] = -1;   // (what was recorded here belonged to the slot's previous use)
+    }
+    ctx->last_stream = st;
+    ctx->use_count = use + 1;
     tm.end(RS_STEP_ROW_RMS);
     // qkv = rope( (x Wqkv'^T) / rms + b )
     tm.begin(RS_STEP_QKV_GEMM);
@@ -689,6 +721,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)));
         e = hipEventCreateWithFlags(&c->slot_done[i], hipEventDisableTiming);
         if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
+        c->slot_recorded_at[i] = -1;
     }
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
