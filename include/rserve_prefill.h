@@ -25,8 +25,9 @@
  *  - Slabs (weights, KV, workspace) must be 256-byte aligned; x and y 16-byte aligned.
  *  - All work is enqueued on the caller's HIP stream (`hip_stream`, a hipStream_t passed as
  *    void*, NULL = the null stream) and the call returns without waiting.  Host-side state
- *    (cache lengths) is advanced at enqueue time.  The caller orders streams; two calls that use
- *    the same rs_kv, the same workspace or the same rs_ctx concurrently on different streams race.
+ *    (cache lengths) is advanced at enqueue time.  The caller orders streams: two calls whose work
+ *    overlaps on the GPU must not share an rs_kv or a workspace (one rs_ctx may serve several
+ *    streams).  The host side is not thread-safe: one thread at a time per rs_ctx.
  *  - Errors are decided on the host BEFORE anything is launched; on any status other than RS_OK
  *    nothing was enqueued and no state changed (RS_EHIP excepted: a launch itself failed).
  *  - bf16 matrices are row-major.  "torch layout" for a weight means [out_features, in_features].
