@@ -530,22 +530,43 @@ __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     float ss = 0.0f;
-    for (int n = lane * 4; n < N; n += WAVE * 4) {
-        const size_t roff = resid_frag ? frag_offset_bytes(m, n, ldr) : ((size_t)m * ldr + n) * 2;
-        const size_t ooff = out_frag ? frag_offset_bytes(m, n, ldo) : ((size_t)m * ldo + n) * 2;
-        bf16x4 r4 = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const char*>(resid) + roff);
-        float v[4] = {bf16_to_f32(r4[0]), bf16_to_f32(r4[1]), bf16_to_f32(r4[2]), bf16_to_f32(r4[3])};
-        for (int s = 0; s < splits; ++s) {
-            f32x4 p = *reinterpret_cast<const f32x4*>(partial + ((size_t)s * M + m) * N + n);
-            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
-        }
-        bf16x4 o = {f32_to_bf16(v[0]), f32_to_bf16(v[1]), f32_to_bf16(v[2]), f32_to_bf16(v[3])};
+    // four column groups per pass: all their loads are issued before the first sum (the kernel is one pass over
+    // (4 splits + 4) N bytes per row; what it has to hide is latency)
+    constexpr int G = 4;
+    for (int n0 = lane * 4; n0 < N; n0 += G * WAVE * 4) {
+        bf16x4 r4[G];
+        f32x4 p[G][4];  // at most 4 planes
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float st = bf16_to_f32(o[e]);
-            ss += st * st;
+        for (int g = 0; g < G; ++g) {
+            const int n = n0 + g * WAVE * 4;
+            if (n < N) {
+                const size_t roff = resid_frag ? frag_offset_bytes(m, n, ldr) : ((size_t)m * ldr + n) * 2;
+                r4[g] = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const char*>(resid) + roff);
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    if (s < splits) p[g][s] = *reinterpret_cast<const f32x4*>(partial + ((size_t)s * M + m) * N + n);
+            }
         }
-        *reinterpret_cast<bf16x4*>(reinterpret_cast<char*>(out) + ooff) = o;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int n = n0 + g * WAVE * 4;
+            if (n < N) {
+                float v[4] = {bf16_to_f32(r4[g][0]), bf16_to_f32(r4[g][1]), bf16_to_f32(r4[g][2]), bf16_to_f32(r4[g][3])};
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    if (s < splits) {
+                        v[0] += p[g][s][0]; v[1] += p[g][s][1]; v[2] += p[g][s][2]; v[3] += p[g][s][3];
+                    }
+                bf16x4 o = {f32_to_bf16(v[0]), f32_to_bf16(v[1]), f32_to_bf16(v[2]), f32_to_bf16(v[3])};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float st = bf16_to_f32(o[e]);
+                    ss += st * st;
+                }
+                const size_t ooff = out_frag ? frag_offset_bytes(m, n, ldo) : ((size_t)m * ldo + n) * 2;
+                *reinterpret_cast<bf16x4*>(reinterpret_cast<char*>(out) + ooff) = o;
+            }
+        }
     }
     if (inv_rms != nullptr) {
         ss = wave_sum(ss);

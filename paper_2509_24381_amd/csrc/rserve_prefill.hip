@@ -200,7 +200,7 @@ double gemm_cost_clocks(const rs_ctx* c, int M, int units, int k_steps, int spli
 }
 
 int choose_splitk(const rs_ctx* c, int M, int units, int k_steps) {
-    if (c->splitk_override > 0) return std::min(c->splitk_override, std::max(1, k_steps));
+    if (c->splitk_override > 0) return std::min(std::min(c->splitk_override, 4), std::max(1, k_steps));  // (the workspace holds 4 planes)
     int best = 1;
     double best_cost = gemm_cost_clocks(c, M, units, k_steps, 1);
     for (int s = 2; s <= 4 && k_steps / s >= 8; ++s) {
