@@ -37,6 +37,38 @@ def test_tracker_case1_consecutive_items_need_no_text_between():
     assert r.schedulable_tokens() == 16
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_paper_walkthroughs_from_the_fixture(seed):
+    """tests/golden/tracker_walkthroughs.json restates the paper's two walkthroughs of the tracker (section 3.1) as event
+    sequences without token counts; with any counts, the oracle and the library must prefill exactly the named segments,
+    whole and in order, at every step."""
+    import json
+    import os
+    rng = np.random.default_rng(seed)
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tracker_walkthroughs.json")
+    for case in json.load(open(path))["cases"]:
+        names = case["segments"]
+        segs = [(n.startswith("MM"), int(rng.integers(1, 50))) for n in names]
+        begin = np.concatenate([[0], np.cumsum([n for _, n in segs])])
+        r = TrackedRequest(7, segs)
+        lib = Scheduler(10 ** 6)
+        lib.add_request(7, segs)
+        q = [r]
+        for step in case["steps"]:
+            for n in step["ready"]:
+                r.mark_ready(names.index(n))
+                lib.mark_ready(7, names.index(n))
+            want = [names.index(n) for n in step["prefilled"]]
+            first = int(begin[want[0]]) if want else r.prefilled
+            count = int(sum(segs[k][1] for k in want))
+            assert r.schedulable_tokens() == count == lib.schedulable_tokens(7), (case["name"], step)
+            s, q = schedule_round(q, 10 ** 6)
+            assert [(x[1], x[2]) for x in s] == [(first, count)], (case["name"], step)
+            entries = lib.next_round()
+            assert [(e[1], e[2]) for e in entries] == [(first, count)], (case["name"], step)
+        assert q == [] and lib.queue_length() == 0, case["name"]
+
+
 def test_out_of_order_encoder_results_do_not_unlock_later_tokens():
     r = TrackedRequest(3, [(T, 2), (M, 5), (M, 6)])
     r.mark_ready(2)
