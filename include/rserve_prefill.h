@@ -146,6 +146,38 @@ rs_status rs_kv_alloc_paged(rs_ctx* ctx, rs_kv_pool* pool, int n_layers, rs_kv**
 /* Bytes of device workspace a call with up to max_tokens rows and max_requests requests needs. */
 size_t rs_workspace_bytes(const rs_ctx* ctx, int max_tokens, int max_requests);
 
+/* 8-bit KV caches.  The paper's systems are configured for the largest KV memory that fits (section 4.1.3) and its
+ * prompts run to tens of thousands of multimodal tokens (sections 2.1.1, 4.1.2); a cache that keeps one byte per element
+ * holds twice the tokens.  Storage format: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinity,
+ * 0x7f / 0xff are NaN, largest value 448), one scale for the keys and one for the values of a cache:
+ *     stored  code  = e4m3( fl32( x * fl32(1 / scale) ) )   x: the bfloat16 K~ or V element; round to nearest, ties to
+ *                                                           even, |.| > 448 saturates to +-448, NaN -> 0x7f
+ *     read    value = bf16( fl32( decode(code) * scale ) )
+ * Every key and value goes through the cache before attention reads it, the running chunk's own rows included, so the
+ * result does not depend on how a prompt is cut into chunks (the contract of section 2.2.1 holds for the quantised
+ * model).  Queries, scores and everything else stay as with a bfloat16 cache.
+ *   rs_kv_fp8_bytes    bytes of device memory for n_layers layers of capacity_tokens tokens (half of rs_kv_bytes).
+ *   rs_kv_alloc_fp8    like rs_kv_alloc; k_scale, v_scale > 0 and finite, with finite reciprocals (RS_EINVAL otherwise).
+ *                      Contiguous only: there is no paged 8-bit cache.
+ *   rs_kv_is_fp8       1 / 0, -1 for a null handle.
+ *   rs_kv_export / rs_kv_import on an 8-bit cache produce / consume bfloat16 rows through the formulas above.
+ *   rs_kv_export_codes, rs_kv_import_codes   the bytes themselves, canonical [len][Hkv][d] uint8 device arrays: what a
+ *                      transfer of the cache to another worker would ship.  RS_ESTATE on a bfloat16 cache.
+ * All caches of one rs_prefill_* call must be of one kind (RS_EINVAL otherwise).  A call on 8-bit caches first expands the
+ * blocks its rows can see into bfloat16 tiles in the workspace (one layer at a time) and runs the ordinary attention
+ * kernel on them, so its workspace must hold, beyond rs_workspace_bytes(), 4 * Hkv * d bytes per visible token, each
+ * request's cached + new tokens rounded up to a multiple of 64; RS_EWORKSPACE otherwise.
+ *   rs_workspace_bytes_fp8kv   that sum for calls whose requests see at most max_visible_tokens tokens in total
+ *                      (sum over the call's requests of cached + new tokens; the rounding is added here). */
+size_t rs_kv_fp8_bytes(const rs_ctx* ctx, int n_layers, int capacity_tokens);
+rs_status rs_kv_alloc_fp8(rs_ctx* ctx, int n_layers, int capacity_tokens, float k_scale, float v_scale, void* dev_mem,
+                          size_t bytes, rs_kv** out);
+int rs_kv_is_fp8(const rs_kv* kv);
+rs_status rs_kv_export_codes(const rs_kv* kv, int layer, void* k_codes_dev, void* v_codes_dev, void* hip_stream);
+rs_status rs_kv_import_codes(rs_kv* kv, int layer, const void* k_codes_dev, const void* v_codes_dev, int n_tokens,
+                             void* hip_stream);
+size_t rs_workspace_bytes_fp8kv(const rs_ctx* ctx, int max_tokens, int max_requests, size_t max_visible_tokens);
+
 /* One chunk of one request through one layer (chunked prefill, section 2.2.1).
  *   x   device bf16 [T, H]: the chunk's rows (image-embedding or text-embedding rows alike), prompt order.
  *   y   device bf16 [T, H]: layer output; may alias x.

@@ -77,7 +77,8 @@ def _bf16(x: np.ndarray) -> np.ndarray:
 def kv_store(x: np.ndarray, scale: float) -> np.ndarray:
     """Codes the cache keeps for the values x (any real array) under `scale`."""
     inv = np.float32(1.0) / np.float32(scale)
-    return e4m3_encode((_bf16(x) * inv).astype(np.float32))
+    with np.errstate(over="ignore", invalid="ignore"):   # (infinities saturate, NaNs stay NaN: both are meant)
+        return e4m3_encode((_bf16(x) * inv).astype(np.float32))
 
 
 def kv_load(codes: np.ndarray, scale: float) -> np.ndarray:

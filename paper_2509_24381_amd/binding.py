@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "rs_kv_free", "rs_kv_len", "rs_kv_capacity", "rs_kv_reset", "rs_kv_truncate", "rs_kv_export", "rs_kv_import",
     "rs_kv_page_bytes", "rs_kv_pool_create", "rs_kv_pool_destroy", "rs_kv_pool_pages", "rs_kv_pool_free_pages",
     "rs_kv_alloc_paged",
+    "rs_kv_fp8_bytes", "rs_kv_alloc_fp8", "rs_kv_is_fp8", "rs_kv_export_codes", "rs_kv_import_codes", "rs_workspace_bytes_fp8kv",
     "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
@@ -106,6 +107,12 @@ def load_library():
         "rs_kv_pool_free_pages": (i, [vp]),
         "rs_kv_alloc_paged": (i, [vp, vp, i, C.POINTER(vp)]),
         "rs_workspace_bytes": (sz, [vp, i, i]),
+        "rs_kv_fp8_bytes": (sz, [vp, i, i]),
+        "rs_kv_alloc_fp8": (i, [vp, i, i, C.c_float, C.c_float, vp, sz, C.POINTER(vp)]),
+        "rs_kv_is_fp8": (i, [vp]),
+        "rs_kv_export_codes": (i, [vp, i, vp, vp, vp]),
+        "rs_kv_import_codes": (i, [vp, i, vp, vp, i, vp]),
+        "rs_workspace_bytes_fp8kv": (sz, [vp, i, i, sz]),
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
@@ -268,6 +275,28 @@ class KVCache:
         _check(load_library().rs_kv_import(self.handle, layer, _ptr(k) if n else None, _ptr(v) if n else None, n,
                                            _stream_handle(stream)))
 
+    @property
+    def is_fp8(self) -> bool:
+        return load_library().rs_kv_is_fp8(self.handle) == 1
+
+    def export_codes(self, layer: int = 0, stream=None):
+        """The stored bytes (K~, V) of an 8-bit cache's `layer` as uint8 tensors [len, Hkv, d] on the device."""
+        import torch
+        n = self.length(layer)
+        cfg = self.ctx.cfg
+        k = torch.empty((n, cfg.n_kv_heads, cfg.head_dim), dtype=torch.uint8, device="cuda")
+        v = torch.empty_like(k)
+        _check(load_library().rs_kv_export_codes(self.handle, layer, _ptr(k) if n else None, _ptr(v) if n else None,
+                                                 _stream_handle(stream)))
+        return k, v
+
+    def import_codes(self, layer: int, k, v, stream=None):
+        """Loads uint8 [n, Hkv, d] device tensors as the stored bytes of an 8-bit cache's `layer`."""
+        n = int(k.shape[0])
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        _check(load_library().rs_kv_import_codes(self.handle, layer, _ptr(k) if n else None, _ptr(v) if n else None, n,
+                                                 _stream_handle(stream)))
+
 
 class Context:
     def __init__(self, cfg: LayerConfig):
@@ -314,9 +343,22 @@ class Context:
         _check(self.lib.rs_kv_alloc(self.handle, n_layers, capacity, _ptr(slab), nbytes, C.byref(h)))
         return KVCache(self, h.value, slab)
 
-    def workspace(self, max_tokens: int, max_requests: int = 1):
+    def workspace(self, max_tokens: int, max_requests: int = 1, fp8_visible_tokens: int = 0):
+        """Device workspace for calls of up to max_tokens rows and max_requests requests; with 8-bit caches also room for
+        the bf16 expansion of fp8_visible_tokens tokens (cached + new, summed over a call's requests)."""
         import torch
-        return torch.empty(self.workspace_bytes(max_tokens, max_requests), dtype=torch.uint8, device="cuda")
+        n = (self.lib.rs_workspace_bytes_fp8kv(self.handle, max_tokens, max_requests, fp8_visible_tokens)
+             if fp8_visible_tokens else self.workspace_bytes(max_tokens, max_requests))
+        return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def kv_alloc_fp8(self, n_layers: int, capacity: int, k_scale: float = 1.0, v_scale: float = 1.0) -> KVCache:
+        """An 8-bit (E4M3) cache: value = decode(code) * scale."""
+        import torch
+        nbytes = self.lib.rs_kv_fp8_bytes(self.handle, n_layers, capacity)
+        slab = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(self.lib.rs_kv_alloc_fp8(self.handle, n_layers, capacity, k_scale, v_scale, _ptr(slab), nbytes, C.byref(h)))
+        return KVCache(self, h.value, slab)
 
     # ---- measurement hook
     def profile_enable(self, step, max_launches: int = 1024, every: int = 1):

@@ -16,6 +16,7 @@
 #include "attention.h"
 #include "common.h"
 #include "elementwise.h"
+#include "kv_fp8.h"
 #include "gemm_strip.h"
 #include "last_error.h"
 
@@ -112,7 +113,11 @@ struct rs_kv {
     std::vector<int> len;
     rs_kv_pool* pool = nullptr;             // paged caches only
     std::vector<std::vector<int>> pages;    // paged: pages[layer][block]
+    bool fp8 = false;                       // one E4M3 byte per element (contiguous caches only); k_bytes counts bytes
+    float k_scale = 1.0f, v_scale = 1.0f;   // 8-bit caches: value = decode(code) * scale
     bool paged() const { return pool != nullptr; }
+    uint8_t* kc_of(int layer) const { return reinterpret_cast<uint8_t*>(base + (size_t)layer * layer_bytes); }
+    uint8_t* vc_of(int layer) const { return reinterpret_cast<uint8_t*>(base + (size_t)layer * layer_bytes + k_bytes); }
     bf16* k_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes); }
     bf16* vt_of(int layer) const { return reinterpret_cast<bf16*>(base + (size_t)layer * layer_bytes + k_bytes); }
     // new pages layer `layer` needs before it can hold n_tokens
@@ -151,7 +156,7 @@ struct rs_kv {
 namespace {
 
 struct DescSizes {
-    size_t reqs, items, vblocks, rowpos, pagetab, mitems, total;
+    size_t reqs, items, vblocks, rowpos, pagetab, mitems, fp8, total;
 };
 
 constexpr int ATT_MAX_PARTS = 8;   // parts per block of a split key range
@@ -173,7 +178,8 @@ DescSizes desc_sizes(const rs_ctx* c, int max_tokens, int max_requests) {
     // block -> page numbers of the paged caches in the call: at most max_pos / 64 + 1 blocks per request
     d.pagetab = align_up(sizeof(int) * (size_t)std::max(max_requests, 1) * ((size_t)c->cfg.max_pos / 64 + 2), 256);
     d.mitems = align_up(sizeof(AttnMergeItem) * attn_split_slots(c), 256);
-    d.total = d.reqs + d.items + d.vblocks + d.rowpos + d.pagetab + d.mitems;
+    d.fp8 = align_up(sizeof(Fp8CacheDesc) * std::max(max_requests, 1), 256);
+    d.total = d.reqs + d.items + d.vblocks + d.rowpos + d.pagetab + d.mitems + d.fp8;
     return d;
 }
 
@@ -243,6 +249,11 @@ WorkspaceLayout ws_layout(const rs_ctx* c, int T, int R) {
     return w;
 }
 
+// bytes of the bfloat16 copy of an 8-bit cache's first n_tokens (whole 64-token blocks, K and V^T of all KV heads)
+size_t fp8_expansion_bytes(const rs_ctx* c, long n_tokens) {
+    return (size_t)2 * align_up((size_t)n_tokens, 64) * c->kv_dim * 2;
+}
+
 template <int EPI>
 rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     a.tiles_m = (a.M + GS_BM - 1) / GS_BM;
@@ -308,11 +319,19 @@ struct StepTimer {
 template <int D>
 rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const ReqDesc* d_reqs,
                                 const AttnItem* d_items, int n_items, const KVBlockItem* d_vb, int n_vb, bool any_paged,
-                                float* split_buf, const AttnMergeItem* d_mitems, int n_mitems, hipStream_t st, const StepTimer& tm) {
+                                float* split_buf, const AttnMergeItem* d_mitems, int n_mitems, const Fp8CacheDesc* d_fp8, int n_reqs,
+                                int n_xblocks, hipStream_t st, const StepTimer& tm) {
     const rs_layer_cfg& f = c->cfg;
     tm.begin(RS_STEP_APPEND_KV);
-    hipLaunchKernelGGL(append_kv_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
-                       d_reqs, d_vb, f.n_q_heads, f.n_kv_heads);
+    if (d_fp8) {  // 8-bit caches: quantise the new rows into them, then expand what the rows can see for the attention kernel
+        hipLaunchKernelGGL(append_kv_fp8_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
+                           d_reqs, d_fp8, d_vb, f.n_q_heads, f.n_kv_heads);
+        RS_HIP(hipGetLastError());
+        hipLaunchKernelGGL(kv_expand_fp8_kernel<D>, dim3(n_xblocks, f.n_kv_heads), dim3(256), 0, st, d_reqs, d_fp8, n_reqs);
+    } else {
+        hipLaunchKernelGGL(append_kv_kernel<D>, dim3(n_vb, f.n_kv_heads), dim3(256), 0, st, (const bf16*)qkv, c->qkv_dim,
+                           d_reqs, d_vb, f.n_q_heads, f.n_kv_heads);
+    }
     RS_HIP(hipGetLastError());
     tm.end(RS_STEP_APPEND_KV);
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
@@ -336,6 +355,39 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
         RS_HIP(hipGetLastError());
     }
     tm.end(RS_STEP_ATTENTION);
+    return RS_OK;
+}
+
+// Tokens [0, len) of an 8-bit cache's layer as bfloat16 values or as codes (whichever pair of outputs is given).
+rs_status fp8_export(const rs_kv* kv, int layer, bf16* k_out, bf16* v_out, uint8_t* kc_out, uint8_t* vc_out, hipStream_t st) {
+    const int n = kv->len[layer];
+    const size_t total = (size_t)n * kv->ctx->kv_dim;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    const int hkv = kv->ctx->cfg.n_kv_heads;
+    if (kv->ctx->cfg.head_dim == 128)
+        hipLaunchKernelGGL(kv_fp8_export_kernel<128>, dim3(blocks), dim3(256), 0, st, (const uint8_t*)kv->kc_of(layer),
+                           (const uint8_t*)kv->vc_of(layer), kv->cap, hkv, kv->k_scale, kv->v_scale, k_out, v_out, kc_out, vc_out, n);
+    else
+        hipLaunchKernelGGL(kv_fp8_export_kernel<64>, dim3(blocks), dim3(256), 0, st, (const uint8_t*)kv->kc_of(layer),
+                           (const uint8_t*)kv->vc_of(layer), kv->cap, hkv, kv->k_scale, kv->v_scale, k_out, v_out, kc_out, vc_out, n);
+    RS_HIP(hipGetLastError());
+    return RS_OK;
+}
+
+// Fills tokens [0, n) of an 8-bit cache's layer from bfloat16 values or from codes (the caller has checked n against cap).
+rs_status fp8_import(rs_kv* kv, int layer, const bf16* k_in, const bf16* v_in, const uint8_t* kc_in, const uint8_t* vc_in, int n,
+                     hipStream_t st) {
+    const size_t total = align_up((size_t)n, 64) * kv->ctx->kv_dim;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    const int hkv = kv->ctx->cfg.n_kv_heads;
+    const float k_inv = 1.0f / kv->k_scale, v_inv = 1.0f / kv->v_scale;
+    if (kv->ctx->cfg.head_dim == 128)
+        hipLaunchKernelGGL(kv_fp8_import_kernel<128>, dim3(blocks), dim3(256), 0, st, kv->kc_of(layer), kv->vc_of(layer), kv->cap, hkv,
+                           k_inv, v_inv, k_in, v_in, kc_in, vc_in, n);
+    else
+        hipLaunchKernelGGL(kv_fp8_import_kernel<64>, dim3(blocks), dim3(256), 0, st, kv->kc_of(layer), kv->vc_of(layer), kv->cap, hkv,
+                           k_inv, v_inv, k_in, v_in, kc_in, vc_in, n);
+    RS_HIP(hipGetLastError());
     return RS_OK;
 }
 
@@ -405,6 +457,9 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
         if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())
             return fail(RS_EINVAL, "the same rs_kv appears twice in one micro-batch");
     }
+    for (int i = 1; i < R; ++i)
+        if (kvs[i]->fp8 != kvs[0]->fp8)
+            return fail(RS_EINVAL, "kvs[%d]: the caches of one call must all be bfloat16 or all be 8-bit", i);
     for (int i = 0; i < R; ++i) {
         const long after = (long)kvs[i]->len[layer] + lens[i];
         if (!kvs[i]->paged() && after > kvs[i]->cap)
@@ -433,7 +488,12 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
     if (!ws) return fail(RS_EINVAL, "workspace is null");
     if (!aligned(ws, 256)) return fail(RS_EINVAL, "workspace must be 256-byte aligned");
     const WorkspaceLayout L = ws_layout(ctx, T, R);
-    if (ws_bytes < L.total) return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, L.total);
+    size_t expansion = 0;  // 8-bit caches: bfloat16 copies of the blocks the call's rows can see
+    for (int i = 0; i < R; ++i)
+        if (kvs[i]->fp8 && lens[i] > 0) expansion += fp8_expansion_bytes(ctx, (long)kvs[i]->len[layer] + lens[i]);
+    if (ws_bytes < L.total + expansion)
+        return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu%s", ws_bytes, L.total + expansion,
+                    expansion ? " (rs_workspace_bytes_fp8kv: the 8-bit caches are expanded there)" : "");
     // (a caller that adds up the page need of several layers reports that shortage before the missing device)
     if (!pages_needed && !ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
     return RS_OK;
@@ -451,6 +511,9 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     std::vector<KVBlockItem> vbs;
     std::vector<int> rowpos;
     std::vector<int> pagetab;
+    std::vector<Fp8CacheDesc> fp8s;
+    int n_xblocks = 0;
+    size_t expansion_off = L.total;
     rowpos.reserve(3 * (size_t)T);
     const DescSizes ds = desc_sizes(ctx, T, R);
     char* wsb = reinterpret_cast<char*>(ws);
@@ -465,6 +528,19 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         kv->take_pages(layer, (long)P + Ti);   // (paged caches; prefill_check has made sure the pool has them)
         ReqDesc d = kv->view(layer, d_pagetab + pagetab.size());
         d.row0 = row0; d.T = Ti; d.P = P;
+        if (kv->fp8) {  // the kernels append to the 8-bit cache and attend to its expansion in the workspace
+            Fp8CacheDesc fc{};
+            fc.kc = kv->kc_of(layer); fc.vc = kv->vc_of(layer); fc.cap = kv->cap; fc.xb0 = n_xblocks;
+            fc.k_scale = kv->k_scale; fc.v_scale = kv->v_scale;
+            fc.k_inv = 1.0f / kv->k_scale; fc.v_inv = 1.0f / kv->v_scale;
+            fp8s.push_back(fc);
+            const size_t plane = fp8_expansion_bytes(ctx, (long)P + Ti) / 2;
+            d.kcache = reinterpret_cast<bf16*>(wsb + expansion_off);
+            d.vtcache = reinterpret_cast<bf16*>(wsb + expansion_off + plane);
+            d.cap = (int)align_up((size_t)P + Ti, 64);
+            expansion_off += 2 * plane;
+            n_xblocks += d.cap / 64;
+        }
         if (kv->paged()) pagetab.insert(pagetab.end(), kv->pages[layer].begin(), kv->pages[layer].end());
         const int ri = (int)reqs.size();
         reqs.push_back(d);
@@ -525,6 +601,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
         sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos ||
         sizeof(int) * pagetab.size() > ds.pagetab || sizeof(AttnMergeItem) * mitems.size() > ds.mitems ||
+        sizeof(Fp8CacheDesc) * fp8s.size() > ds.fp8 || (!fp8s.empty() && fp8s.size() != reqs.size()) ||
         ds.total > ctx->slot_bytes)
         return fail(RS_EINVAL, "internal: descriptor sizing");
 
@@ -559,6 +636,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     memcpy(stage + ds.reqs + ds.items + ds.vblocks, rowpos.data(), sizeof(int) * rowpos.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos, pagetab.data(), sizeof(int) * pagetab.size());
     memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab, mitems.data(), sizeof(AttnMergeItem) * mitems.size());
+    memcpy(stage + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab + ds.mitems, fp8s.data(), sizeof(Fp8CacheDesc) * fp8s.size());
     // (the first kernel below copies the staged descriptors into the workspace; the slot is free again once it has run)
     const ReqDesc* d_reqs = reinterpret_cast<const ReqDesc*>(wsb + L.desc);
     const AttnItem* d_items = reinterpret_cast<const AttnItem*>(wsb + L.desc + ds.reqs);
@@ -567,6 +645,8 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     const AttnMergeItem* d_mitems =
         reinterpret_cast<const AttnMergeItem*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab);
     float* attn_split = reinterpret_cast<float*>(wsb + L.attn_split);
+    const Fp8CacheDesc* d_fp8 = fp8s.empty() ? nullptr :
+        reinterpret_cast<const Fp8CacheDesc*>(wsb + L.desc + ds.reqs + ds.items + ds.vblocks + ds.rowpos + ds.pagetab + ds.mitems);
 
     bf16* qkv = reinterpret_cast<bf16*>(wsb + L.qkv);
     bf16* xf = reinterpret_cast<bf16*>(wsb + L.xf);
@@ -616,10 +696,10 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     // cache append, attention
     if (f.head_dim == 128)
         s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
-                                       attn_split, d_mitems, (int)mitems.size(), st, tm);
+                                       attn_split, d_mitems, (int)mitems.size(), d_fp8, (int)reqs.size(), n_xblocks, st, tm);
     else
         s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
-                                      attn_split, d_mitems, (int)mitems.size(), st, tm);
+                                      attn_split, d_mitems, (int)mitems.size(), d_fp8, (int)reqs.size(), n_xblocks, st, tm);
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
@@ -850,6 +930,41 @@ rs_status rs_kv_alloc(rs_ctx* c, int n_layers, int capacity_tokens, void* dev_me
     return RS_OK;
 }
 
+size_t rs_kv_fp8_bytes(const rs_ctx* c, int n_layers, int capacity_tokens) {
+    if (!c || n_layers <= 0 || capacity_tokens <= 0) return 0;
+    const size_t cap = align_up((size_t)capacity_tokens, 64);
+    const size_t plane = align_up(cap * c->kv_dim, 256);
+    return 2 * plane * n_layers;
+}
+
+rs_status rs_kv_alloc_fp8(rs_ctx* c, int n_layers, int capacity_tokens, float k_scale, float v_scale, void* dev_mem, size_t bytes,
+                          rs_kv** out) {
+    if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
+    *out = nullptr;
+    if (n_layers <= 0 || capacity_tokens <= 0) return fail(RS_EINVAL, "n_layers and capacity_tokens must be positive");
+    if (!(k_scale > 0.0f) || !(v_scale > 0.0f) || !std::isfinite(k_scale) || !std::isfinite(v_scale) ||
+        !std::isfinite(1.0f / k_scale) || !std::isfinite(1.0f / v_scale))
+        return fail(RS_EINVAL, "k_scale = %g and v_scale = %g must be positive, finite and have a finite reciprocal", k_scale, v_scale);
+    if (!dev_mem || !aligned(dev_mem, 256)) return fail(RS_EINVAL, "dev_mem must be a 256-byte aligned device pointer");
+    const size_t need = rs_kv_fp8_bytes(c, n_layers, capacity_tokens);
+    if (bytes < need) return fail(RS_EWORKSPACE, "KV slab has %zu bytes, need %zu", bytes, need);
+    rs_kv* kv = new rs_kv();
+    kv->ctx = c;
+    kv->n_layers = n_layers;
+    kv->cap = (int)align_up((size_t)capacity_tokens, 64);
+    kv->base = reinterpret_cast<char*>(dev_mem);
+    kv->k_bytes = align_up((size_t)kv->cap * c->kv_dim, 256);
+    kv->layer_bytes = 2 * kv->k_bytes;
+    kv->len.assign(n_layers, 0);
+    kv->fp8 = true;
+    kv->k_scale = k_scale;
+    kv->v_scale = v_scale;
+    *out = kv;
+    return RS_OK;
+}
+
+int rs_kv_is_fp8(const rs_kv* kv) { return kv ? (kv->fp8 ? 1 : 0) : -1; }
+
 size_t rs_kv_page_bytes(const rs_ctx* c) {
     if (!c) return 0;
     return (size_t)2 * c->cfg.n_kv_heads * 64 * c->cfg.head_dim * 2;
@@ -953,6 +1068,7 @@ rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out, void* v_out, voi
     const rs_layer_cfg& f = kv->ctx->cfg;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int kv_dim = kv->ctx->kv_dim;
+    if (kv->fp8) return fp8_export(kv, layer, (bf16*)k_out, (bf16*)v_out, nullptr, nullptr, st);
     for_each_kv_window(kv, layer, n, [&](const ReqDesc& rq, const KVPageWindow& win, int b0, int t0, int nt) {
         const size_t total = (size_t)nt * kv_dim;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
@@ -988,6 +1104,11 @@ rs_status rs_kv_import(rs_kv* kv, int layer, const void* k, const void* v, int n
         kv->take_pages(layer, n_tokens);
         kv->give_back_pages(layer, n_tokens);
     }
+    if (kv->fp8) {
+        const rs_status s = fp8_import(kv, layer, (const bf16*)k, (const bf16*)v, nullptr, nullptr, n_tokens, st);
+        if (s == RS_OK) kv->len[layer] = n_tokens;
+        return s;
+    }
     for_each_kv_window(kv, layer, n_tokens, [&](const ReqDesc& rq, const KVPageWindow& win, int b0, int t0, int nt) {
         const size_t total = align_up((size_t)nt, 64) * kv_dim;
         const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
@@ -999,6 +1120,35 @@ rs_status rs_kv_import(rs_kv* kv, int layer, const void* k, const void* v, int n
     RS_HIP(hipGetLastError());
     kv->len[layer] = n_tokens;
     return RS_OK;
+}
+
+rs_status rs_kv_export_codes(const rs_kv* kv, int layer, void* k_codes, void* v_codes, void* stream) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (!kv->fp8) return fail(RS_ESTATE, "not an 8-bit cache");
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    if (kv->len[layer] == 0) return RS_OK;
+    if (!k_codes || !v_codes) return fail(RS_EINVAL, "k_codes / v_codes is null");
+    if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
+    return fp8_export(kv, layer, nullptr, nullptr, (uint8_t*)k_codes, (uint8_t*)v_codes, reinterpret_cast<hipStream_t>(stream));
+}
+
+rs_status rs_kv_import_codes(rs_kv* kv, int layer, const void* k_codes, const void* v_codes, int n_tokens, void* stream) {
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (!kv->fp8) return fail(RS_ESTATE, "not an 8-bit cache");
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
+    if (n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
+    if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
+    if (n_tokens == 0) {
+        kv->len[layer] = 0;
+        return RS_OK;
+    }
+    if (!k_codes || !v_codes) return fail(RS_EINVAL, "k_codes / v_codes is null");
+    if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
+    const rs_status s = fp8_import(kv, layer, nullptr, nullptr, (const uint8_t*)k_codes, (const uint8_t*)v_codes, n_tokens,
+                                   reinterpret_cast<hipStream_t>(stream));
+    if (s == RS_OK) kv->len[layer] = n_tokens;
+    return s;
 }
 
 rs_status rs_profile_enable(rs_ctx* c, int step, int max_launches) {
@@ -1043,6 +1193,12 @@ rs_status rs_profile_read(rs_ctx* c, double* total_ms, int* launches) {
 size_t rs_workspace_bytes(const rs_ctx* c, int max_tokens, int max_requests) {
     if (!c || max_tokens <= 0 || max_requests <= 0) return 0;
     return ws_layout(c, max_tokens, max_requests).total;
+}
+
+size_t rs_workspace_bytes_fp8kv(const rs_ctx* c, int max_tokens, int max_requests, size_t max_visible_tokens) {
+    if (!c || max_tokens <= 0 || max_requests <= 0) return 0;
+    // every request's share is rounded up to whole 64-token blocks
+    return ws_layout(c, max_tokens, max_requests).total + fp8_expansion_bytes(c, (long)max_visible_tokens + 63L * max_requests);
 }
 
 rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv, const void* x, int T, void* y,

@@ -47,12 +47,13 @@ class LayerStack:
     """L decoder layers of one shape on the GPU, plus a workspace sized for the token budget."""
 
     def __init__(self, shape, layer_weights: Sequence, *, max_tokens: int, max_requests: int = 64,
-                 max_pos: int = 32768, qkv_bias: bool = False):
+                 max_pos: int = 32768, qkv_bias: bool = False, fp8_visible_tokens: int = 0):
         self.shape = shape
         self.ctx = Context(config_for(shape, qkv_bias=qkv_bias, max_tokens=max_tokens, max_requests=max_requests,
                                       max_pos=max_pos))
         self.layers: List[PackedWeights] = [pack_layer(self.ctx, w) for w in layer_weights]
-        self.ws = self.ctx.workspace(max_tokens, max_requests)
+        # (fp8_visible_tokens: room for the bf16 expansion that calls on 8-bit caches need, see Context.workspace)
+        self.ws = self.ctx.workspace(max_tokens, max_requests, fp8_visible_tokens)
 
     @property
     def n_layers(self) -> int:
@@ -60,6 +61,9 @@ class LayerStack:
 
     def new_cache(self, capacity: int) -> KVCache:
         return self.ctx.kv_alloc(self.n_layers, capacity)
+
+    def new_cache_fp8(self, capacity: int, k_scale: float = 1.0, v_scale: float = 1.0) -> KVCache:
+        return self.ctx.kv_alloc_fp8(self.n_layers, capacity, k_scale, v_scale)
 
     def new_pool(self, n_pages: int) -> KVPool:
         """A pool of KV pages (64 tokens of one layer each); `pool.new_cache(stack.n_layers)` gives growable caches."""

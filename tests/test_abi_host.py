@@ -264,3 +264,60 @@ def test_valid_call_without_a_gpu_fails_loudly(lib):
         ctx.prefill_chunk(fake_weights(), 0, kv, X(), X(), FakeDeviceMemory())
     assert e.value.status_name == "RS_EHIP"
     assert kv.length(0) == 0
+
+
+def test_8bit_cache_argument_checks_on_the_host(lib):
+    """Sizes, scales, the one-kind-per-call rule and the workspace an 8-bit cache's expansion needs: all decided before a
+    device is touched."""
+    ctx = Context(tiny_cfg())
+    assert lib.rs_kv_fp8_bytes(ctx.handle, 2, 100) == ctx.kv_bytes(2, 100) // 2 == 2 * 2 * 128 * 128
+    assert lib.rs_kv_fp8_bytes(ctx.handle, 0, 100) == 0 and lib.rs_kv_fp8_bytes(None, 2, 100) == 0
+    h = C.c_void_p()
+    need = lib.rs_kv_fp8_bytes(ctx.handle, 2, 100)
+    for ks, vs in ((0.0, 1.0), (1.0, -1.0), (float("inf"), 1.0), (float("nan"), 1.0), (1.0, 1e-45)):
+        assert lib.rs_kv_alloc_fp8(ctx.handle, 2, 100, ks, vs, 0x7D0000000000, need, C.byref(h)) == -1, (ks, vs)
+    assert lib.rs_kv_alloc_fp8(ctx.handle, 2, 100, 1.0, 1.0, 0x7D0000000010, need, C.byref(h)) == -1      # misaligned
+    assert lib.rs_kv_alloc_fp8(ctx.handle, 2, 100, 1.0, 1.0, 0x7D0000000000, need - 1, C.byref(h)) == -3
+    assert lib.rs_kv_alloc_fp8(ctx.handle, 2, 100, 0.5, 2.0, 0x7D0000000000, need, C.byref(h)) == 0, lib.rs_last_error()
+    kv8 = binding.KVCache(ctx, h.value, None)
+    assert kv8.is_fp8 and kv8.capacity == 128 and kv8.length(1) == 0
+    kv16 = make_kv(lib, ctx)
+    assert not kv16.is_fp8 and lib.rs_kv_is_fp8(None) == -1
+    assert lib.rs_kv_export_codes(kv16.handle, 0, 0x7B0000000000, 0x7B0000100000, None) == -4           # RS_ESTATE
+    assert lib.rs_kv_import_codes(kv16.handle, 0, 0x7B0000000000, 0x7B0000100000, 10, None) == -4
+    assert lib.rs_kv_import_codes(kv8.handle, 0, 0x7B0000000000, 0x7B0000100000, 129, None) == -2        # beyond capacity
+    assert lib.rs_kv_import_codes(kv8.handle, 2, 0x7B0000000000, 0x7B0000100000, 10, None) == -1
+    assert lib.rs_kv_import_codes(kv8.handle, 0, None, None, 0, None) == 0
+    assert lib.rs_kv_export_codes(kv8.handle, 0, None, None, None) == 0                                 # empty: nothing to do
+    # workspace: rs_workspace_bytes plus 4 * Hkv * d bytes per visible token, each request rounded up to 64 tokens
+    base = ctx.workspace_bytes(128, 4)
+    per_token = 4 * 2 * 64
+    assert lib.rs_workspace_bytes_fp8kv(ctx.handle, 128, 4, 0) == base + per_token * 256      # 4 x 63 -> 256 tokens of rounding
+    assert lib.rs_workspace_bytes_fp8kv(ctx.handle, 128, 1, 1) == ctx.workspace_bytes(128, 1) + per_token * 64
+    assert lib.rs_workspace_bytes_fp8kv(ctx.handle, 128, 1, 65) == ctx.workspace_bytes(128, 1) + per_token * 128
+    w = fake_weights()
+
+    class X:
+        def __init__(self, t):
+            self.shape = (t, 256)
+        def data_ptr(self):
+            return 0x7B0000000000
+
+    class Mem(FakeDeviceMemory):
+        def __init__(self, n):
+            super().__init__()
+            self.n = n
+        def numel(self):
+            return self.n
+
+    def status_of(fn):
+        with pytest.raises(RsError) as e:
+            fn()
+        return e.value.status_name
+
+    assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8, kv16], [10, 10], X(20), X(20), Mem(1 << 40))) == "RS_EINVAL"
+    ws1 = ctx.workspace_bytes(70, 1)
+    assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8], [70], X(70), X(70), Mem(ws1))) == "RS_EWORKSPACE"
+    assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8], [70], X(70), X(70), Mem(ws1 + per_token * 128 - 1))) == "RS_EWORKSPACE"
+    assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8], [70], X(70), X(70), Mem(ws1 + per_token * 128))) == "RS_EHIP"
+    assert kv8.length(0) == 0

@@ -253,7 +253,8 @@ def test_alternative_kernel_paths_meet_the_same_bar(env):
     workload-1 parity test on its own (run in a child process because the choice is read once per process)."""
     child_env = dict(os.environ, **env)
     proc = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", os.path.join(ROOT, "tests", "test_gpu_parity.py"),
-                           os.path.join(ROOT, "tests", "test_gpu_paged_kv.py"),
-                           "-k", "workload1 or small_ragged or two_layers or odd_head or bit_for_bit or splits_the_key or growing"],
+                           os.path.join(ROOT, "tests", "test_gpu_paged_kv.py"), os.path.join(ROOT, "tests", "test_gpu_fp8_kv.py"),
+                           "-k", "workload1 or small_ragged or two_layers or odd_head or bit_for_bit or splits_the_key or growing "
+                                 "or long_8bit or quantised_oracle"],
                           cwd=ROOT, env=child_env, capture_output=True, text=True, timeout=600)
     assert proc.returncode == 0, proc.stdout[-2000:] + proc.stderr[-2000:]
