@@ -95,8 +95,9 @@ def test_store_and_load_follow_their_formula_on_hand_values():
     # scale 0.5: 0.3 -> bf16 0.30078125 -> * 2 = 0.6015625 -> nearest of {0.5625, 0.625} is 0.625 (0x32) -> * 0.5
     assert kv_store(np.array([0.3]), 0.5)[0] == 0x32
     assert kv_load(np.array([0x32], dtype=np.uint8), 0.5)[0] == 0.3125
-    # the bf16 rounding comes first: 1.06 is above the tie 1.0625 only before it (bf16(1.06) = 1.0625 -> tie -> 1.0)
-    assert kv_store(np.array([1.06]), 1.0)[0] == 0x38
+    # the bf16 rounding comes first: 1.064 lies above the tie 1.0625 (it would go up to 1.125), but bf16(1.064) = 1.0625
+    # is the tie itself and goes to the even mantissa, 1.0
+    assert kv_store(np.array([1.064]), 1.0)[0] == 0x38 and e4m3_encode(np.array([1.064]))[0] == 0x39
     # relative error of a stored value: half a step of 2^-3 relative to the binade, i.e. at most 1/16 + bf16 rounding
     rng = np.random.default_rng(2)
     x = rng.normal(0, 2.0, 20000)
@@ -176,3 +177,88 @@ def test_scale_moves_the_range(scale):
     c = kv_store(x, scale)
     assert list(c[:3]) == [0x7E, 0x7E, 0xFE]
     assert math.isclose(kv_load(c, scale)[3], 0.25 * scale, rel_tol=2.0 ** -8)
+
+
+# ------------------------------------------------------------------ the pins above can fail
+def _decode_bias_8(codes):
+    return e4m3_decode(codes) / 2.0                      # the other common 8-bit layout's exponent bias
+
+
+def _decode_no_subnormals(codes):
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    v = e4m3_decode(codes)
+    m, e = c & 7, (c >> 3) & 15
+    return np.where(e == 0, np.where(c >= 128, -1.0, 1.0) * (1.0 + m / 8.0) * 2.0 ** -7 * (m > 0), v)
+
+
+def _decode_with_infinity(codes):
+    c = np.asarray(codes, dtype=np.uint8)
+    return np.where((c & 0x7F) == 0x78, np.where(c >= 128, -np.inf, np.inf), e4m3_decode(codes))
+
+
+def _encode_truncating(x):
+    import oracle.fp8_kv as m
+    x = np.asarray(x, dtype=np.float64)
+    mags = m._finite_magnitudes()
+    a = np.minimum(np.abs(np.where(np.isnan(x), 0.0, x)), 448.0)
+    lo = np.clip(np.searchsorted(mags, a, side="right") - 1, 0, len(mags) - 1)
+    return np.where(np.isnan(x), 0x7F, lo | np.where(np.signbit(x), 128, 0)).astype(np.uint8)
+
+
+def _encode_ties_away(x):
+    x = np.asarray(x, dtype=np.float64)
+    return e4m3_encode(np.where(np.isnan(x), x, x * (1.0 + 2.0 ** -30)))
+
+
+def _encode_overflow_to_nan(x):
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(np.abs(x) > 464.0, 0x7F, e4m3_encode(x)).astype(np.uint8)
+
+
+def _encode_drops_sign_of_zero(x):
+    c = e4m3_encode(x)
+    return np.where(c == 0x80, 0x00, c).astype(np.uint8)
+
+
+def _store_without_bf16_rounding(x, scale):
+    inv = np.float32(1.0) / np.float32(scale)
+    return e4m3_encode((np.asarray(x, dtype=np.float32) * inv).astype(np.float32))
+
+
+def _store_multiplies_by_scale(x, scale):
+    import oracle.fp8_kv as m
+    return e4m3_encode((m._bf16(x) * np.float32(scale)).astype(np.float32))
+
+
+def _load_without_bf16_rounding(codes, scale):
+    return (e4m3_decode(codes).astype(np.float32) * np.float32(scale)).astype(np.float64)
+
+
+FP8_MUTANTS = [("e4m3_decode", _decode_bias_8), ("e4m3_decode", _decode_no_subnormals), ("e4m3_decode", _decode_with_infinity),
+               ("e4m3_encode", _encode_truncating), ("e4m3_encode", _encode_ties_away), ("e4m3_encode", _encode_overflow_to_nan),
+               ("e4m3_encode", _encode_drops_sign_of_zero), ("kv_store", _store_without_bf16_rounding),
+               ("kv_store", _store_multiplies_by_scale), ("kv_load", _load_without_bf16_rounding)]
+
+
+@pytest.mark.parametrize("name,mutant", FP8_MUTANTS, ids=[f.__name__.lstrip("_") for _, f in FP8_MUTANTS])
+def test_planted_mistake_in_the_codec_is_caught(monkeypatch, name, mutant):
+    """Each plausible mistake, planted in the oracle module (and in this module's imported names), must trip a pin."""
+    import sys
+    import oracle.fp8_kv as m
+    me = sys.modules[__name__]
+    monkeypatch.setattr(m, name, mutant)
+    monkeypatch.setattr(me, name, mutant)
+    calls = [test_decode_values_the_format_fixes, test_decode_matches_library_float8, test_encode_round_trips_every_code,
+             test_encode_is_the_nearest_code_by_exhaustive_search,
+             test_encode_ties_go_to_the_even_mantissa_and_large_values_saturate,
+             test_encode_matches_library_float8_on_every_bf16_value_in_range, test_encode_is_monotone_and_odd,
+             test_store_and_load_follow_their_formula_on_hand_values, lambda: test_scale_moves_the_range(0.125)]
+    caught = []
+    for call in calls:
+        try:
+            call()
+        except AssertionError:
+            caught.append(call)
+        except Exception:
+            caught.append(call)
+    assert caught, f"no pin noticed {mutant.__name__}"
