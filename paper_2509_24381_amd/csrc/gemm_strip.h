@@ -13,17 +13,19 @@
 // start and end at any unit.  The 4 wavefronts of a workgroup are stacked along the token dimension (64 rows each, 2 x NT
 // MFMA tiles, up to 256 fp32 accumulators per lane, one wavefront per SIMD).
 //
-// Operand slabs travel global -> LDS directly (buffer_load ... lds, 16 bytes per lane, no VGPR staging) through a ring of
-// 4 stages of K = 32; the load stream runs three stages ahead of the multiply and does not stop at tile boundaries, so
-// the next tile's first slabs arrive while the current tile's epilogue runs.  Rows past M fall outside the buffer resource
-// and read as zeros.  A stage row is 64 bytes; 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3), which keeps both
-// the linear 1 KB-per-wavefront DMA fills and the row-strided fragment reads free of bank conflicts.
+// The weight rows travel global -> LDS directly (buffer_load ... lds, 16 bytes per lane, no VGPR staging) through a ring
+// of slots, one step of K = 64 per slot; the load stream runs SLOTS - 1 steps ahead of the multiply and does not stop at
+// tile boundaries, so the next tile's first slabs arrive while the current tile's epilogue runs.  A slot row is 128
+// bytes; 16-byte chunk c of row r sits at place c ^ ((r >> 1) & 7), which keeps both the linear 1 KB-per-wavefront DMA
+// fills and the row-strided fragment reads free of bank conflicts.  The token rows are stored fragment-major and go
+// global -> registers, XD steps ahead.  Rows past M fall outside the buffer resource and read as zeros.
 //
 // The compiler cannot see LDS written by DMA (it would wait for every outstanding load before any LDS read), so the
-// fragment reads are inline ds_read_b128 and the waits are explicit: loads retire in order and every wavefront issues the
-// same number per stage (4 for X, LW for W, the ones beyond the tile's rows aimed outside the buffer), so "vmcnt(8 + LW)"
-// in the middle of stage s means stage s+1 has landed.  One memory instruction rides behind each MFMA, pinned with
-// scheduling fences, so its issue latency overlaps the matrix pipe.
+// fragment reads are inline ds_read_b128 and the wait for the next weight step is explicit: loads retire in order and
+// every wavefront issues the same number per step (8 for X, NT for W, the ones beyond the tile's rows aimed outside the
+// buffer), so a vmcnt that leaves this step's token loads and the loads of the SLOTS - 3 steps before it in flight means
+// the next weight step has landed.  One memory instruction rides behind each MFMA, pinned with scheduling fences, so
+// its issue latency overlaps the matrix pipe.
 #pragma once
 #include <type_traits>
 
@@ -65,10 +67,20 @@ struct GemmArgs {
 
 constexpr int GS_BM = 256;
 constexpr int GS_BK = 64;                            // K per pipeline step
-constexpr int GS_MAX_NT = 8;                         // units per tile
-constexpr int GS_SLOT_BYTES = GS_MAX_NT * 32 * GS_BK * 2;  // 32 KB: up to 256 weight rows of one step
+// The kernel comes in two geometries.  Wide: tiles of up to 8 units, a ring of 4 slots of 32 KB (three steps of weight
+// look-ahead), token fragments loaded one step ahead, one workgroup per compute unit with up to 512 registers per lane.
+// Narrow, for launches whose strips hold at most 2 units (few token rows spread over the whole chip): a step is then only
+// 8 or 16 MFMAs per wavefront, shorter than the memory latency one step of look-ahead would have to cover, so the ring has
+// 8 slots of 8 KB (seven steps of weight look-ahead), the token fragments are loaded three steps ahead (the accumulators
+// leave the registers for that), and two workgroups share a compute unit.
+constexpr int GS_MAX_NT = 8;                         // units per tile (wide)
 constexpr int GS_SLOTS = 4;
-constexpr int GS_LDS_BYTES = GS_SLOTS * GS_SLOT_BYTES;
+constexpr int GS_NARROW_NT = 2;
+constexpr int GS_NARROW_SLOTS = 8;
+constexpr int GS_NARROW_XD = 3;                      // steps the token fragments are loaded ahead (narrow)
+constexpr int gs_lds_bytes(int max_nt, int slots) { return slots * max_nt * 32 * GS_BK * 2; }
+constexpr int GS_LDS_BYTES = gs_lds_bytes(GS_MAX_NT, GS_SLOTS);                    // 128 KB
+constexpr int GS_NARROW_LDS_BYTES = gs_lds_bytes(GS_NARROW_NT, GS_NARROW_SLOTS);   // 64 KB
 
 // silu(g) = g / (1 + 2^(-g log2 e)) with the raw v_exp_f32 / v_rcp_f32 instructions (1 ulp each; the result is rounded to bf16)
 RS_DEVICE float silu_f32(float g) {
@@ -269,8 +281,14 @@ RS_DEVICE void tie_wait_lgkm0(bf16x8 (&w)[NT]) {
 #pragma unroll
     for (int i = 1; i < NT; ++i) asm volatile("" : "+v"(w[i]));
 }
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
+template <int EPI, int MAXNT = GS_MAX_NT, int SLOTS = GS_SLOTS, int OCC = 1, int XD = 1>
+__global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
+    constexpr int XB = XD + 1;   // token-fragment buffers: the step being multiplied and the XD steps in flight behind it
+    constexpr int SLOT_BYTES = MAXNT * 32 * GS_BK * 2;   // up to 32 MAXNT weight rows of one step
+    constexpr int RING_BYTES = SLOTS * SLOT_BYTES;       // a power of two
+    constexpr int AHEAD = SLOTS - 1;                     // steps the weight stream runs ahead of the multiply
+    static_assert((RING_BYTES & (RING_BYTES - 1)) == 0 && AHEAD >= 3, "ring geometry");
+    static_assert(8 + (AHEAD - 2) * (MAXNT + 8) <= 63, "the wait for the next weight step must fit the vmcnt field");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef __attribute__((address_space(3))) void* lds_ptr;
     const int tid = threadIdx.x;
@@ -302,7 +320,7 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     const int u_first = strip * ub + min(strip, ur);
     const int u_count = ub + (strip < ur ? 1 : 0);
     if (u_count == 0) return;  // more strips than units: never launched this way, and uniform for the whole workgroup
-    const int ntiles = (u_count + GS_MAX_NT - 1) / GS_MAX_NT;
+    const int ntiles = (u_count + MAXNT - 1) / MAXNT;
     const int tb = u_count / ntiles;
     const int n_small = ntiles - u_count % ntiles;  // tiles [0, n_small) have tb units, the rest tb + 1
 
@@ -326,7 +344,7 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     const uint32_t xv1 = xv0 + x_block_bytes;
     uint32_t x_koff = xk0;  // byte offset of the next step to load inside a token block
     int x_s = 0;
-    bf16x8 xA[2][4], xB[2][4];
+    bf16x8 xbuf[XB][2][4];
     auto load_x = [&](auto oc, bf16x8 (&xn)[2][4]) {  // load number o of a step: (j, kk) = (o >> 2, o & 3)
         constexpr int o = decltype(oc)::value;
         const uint32_t voff = ((o >> 2) ? xv1 : xv0) + (uint32_t)((o & 3) * 1024);
@@ -363,7 +381,7 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
         d_vw = in_strip ? vw0 : DEAD;
     };
     auto stream_advance = [&]() {
-        d_slot = (d_slot + GS_SLOT_BYTES) & (GS_LDS_BYTES - 1);
+        d_slot = (d_slot + SLOT_BYTES) & (RING_BYTES - 1);
         d_koff += GS_BK * 2;
         if (__builtin_expect(++d_s == ns, 0)) {
             d_s = 0;
@@ -386,18 +404,19 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
         aw[kk] = lds0 + (uint32_t)l32 * 128u + (((uint32_t)(kk * 2 + half) ^ (uint32_t)((l32 >> 1) & 7)) * 16u);
     uint32_t c_slot = 0;  // ring slot of the step being multiplied
 
-    // ---- fill the pipeline: W(0), W(1), X(0), W(2)
+    // ---- fill the pipeline: W(0) .. W(AHEAD - 2), X(0) .. X(XD - 1), W(AHEAD - 1)
     stream_enter_tile();
     auto prologue_w = [&]() {
-        static_for<0, GS_MAX_NT>([&](auto kc) {
+        static_for<0, MAXNT>([&](auto kc) {
             if (decltype(kc)::value < d_nt) load_w(kc);
         });
         stream_advance();
     };
-    prologue_w();
-    prologue_w();
-    static_for<0, 8>([&](auto oc) { load_x(oc, xA); });
-    x_advance();
+    static_for<0, AHEAD - 1>([&](auto) { prologue_w(); });
+    static_for<0, XD>([&](auto bc) {
+        static_for<0, 8>([&](auto oc) { load_x(oc, xbuf[decltype(bc)::value]); });
+        x_advance();
+    });
     prologue_w();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -442,7 +461,7 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
         // barrier in the middle publishes the weights of the next step, whose first fragments are read behind k-step 3
         // together with the DMA of the weights three steps ahead
         auto step = [&](bf16x8 (&xc)[2][4], bf16x8 (&xn)[2][4]) {
-            const uint32_t n_slot = (c_slot + GS_SLOT_BYTES) & (GS_LDS_BYTES - 1);
+            const uint32_t n_slot = (c_slot + SLOT_BYTES) & (RING_BYTES - 1);
             tie_wait_lgkm0<NT>(wa);
             phase(std::integral_constant<int, 0>{}, wa, xc, wb, aw[1] + c_slot, std::integral_constant<int, 4>{},
                   [&](auto ec) { load_x(ec, xn); });
@@ -451,7 +470,9 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
                   [&](auto ec) { load_x(std::integral_constant<int, decltype(ec)::value + 4>{}, xn); });
             x_advance();
             tie_wait_lgkm0<NT>(wa);  // also: every LDS read of k-steps 0..2 has landed
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(16 + NT) : "memory");  // this wavefront's share of the next W step
+            // this wavefront's share of the next W step has landed when at most this step's 8 token loads and the loads of
+            // the AHEAD - 2 steps before it (NT weight, 8 token) are still in flight
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 + (AHEAD - 2) * (NT + 8)) : "memory");
             asm volatile("s_barrier" ::: "memory");
             RS_FENCE();
             constexpr int W_A = (NT + 1) / 2, W_B = NT - W_A;
@@ -467,29 +488,47 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
                           load_w(std::integral_constant<int, decltype(ec)::value + W_A>{});
                       } else {
                           if (__builtin_expect(d_nt > NT, 0))
-                              load_w(std::integral_constant<int, NT < GS_MAX_NT ? NT : 0>{});  // the stream is in a wider tile
+                              load_w(std::integral_constant<int, NT < MAXNT ? NT : 0>{});  // the stream is in a wider tile
                           stream_advance();
                       }
                   });
             c_slot = n_slot;
         };
 
-        // tile start: xA holds (or is receiving) the tile's first token fragments; its first weight step was published by
-        // the previous tile's last barrier (by the prologue for the first tile)
+        // tile start: xbuf[0 .. XD - 1] hold (or are receiving) the tile's first token fragments; its first weight step was
+        // published by the previous tile's last barrier (by the prologue for the first tile)
         asm volatile("s_barrier" ::: "memory");
         static_for<0, NT>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
+        // step number s multiplies buffer s mod XB and loads the fragments of step s + XD into the buffer step s - 1 used
         int s = 0;
-        for (; s + 1 < ns; s += 2) {
-            step(xA, xB);
-            step(xB, xA);
-        }
-        if (s < ns) {  // odd number of steps: one more, then move the fragments in flight back to xA
-            step(xA, xB);
+        for (; s + XB <= ns; s += XB)
+            static_for<0, XB>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                step(xbuf[u], xbuf[(u + XD) % XB]);
+            });
+        // the steps left over, then the fragments in flight move to where the next tile expects them (buffer 0 first)
+        static_for<1, XB>([&](auto rc) {
+            constexpr int R = decltype(rc)::value;
+            if (ns - s == R) {
+                static_for<0, R>([&](auto uc) {
+                    constexpr int u = decltype(uc)::value;
+                    step(xbuf[u], xbuf[(u + XD) % XB]);
+                });
+                bf16x8 moved[XB][2][4];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                for (int b = 0; b < XD; ++b)      // (the buffer multiplied last holds nothing that is still needed)
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) xA[j][kk] = xB[j][kk];
-        }
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) moved[b][j][kk] = xbuf[(b + R) % XB][j][kk];
+#pragma unroll
+                for (int b = 0; b < XD; ++b)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) xbuf[b][j][kk] = moved[b][j][kk];
+            }
+        });
         tie_wait_lgkm0<NT>(wa);  // the look-ahead read behind the last step (discarded: the next tile reads its own)
         gemm_epilogue<EPI, NT>(a, acc, m0 + wave * 64, unit0, half, l32, split);
     };
@@ -497,6 +536,10 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
     for (int t = 0; t < ntiles; ++t) {
         const int nt = tb + (t >= n_small ? 1 : 0);
         const int unit0 = u_first + t * tb + max(t - n_small, 0);
+        if constexpr (MAXNT == 2) {
+            if (nt == 1) run_tile(std::integral_constant<int, 1>{}, unit0);
+            else run_tile(std::integral_constant<int, 2>{}, unit0);
+        } else
         switch (nt) {
             case 1: run_tile(std::integral_constant<int, 1>{}, unit0); break;
             case 2: run_tile(std::integral_constant<int, 2>{}, unit0); break;
@@ -520,25 +563,31 @@ __global__ __launch_bounds__(256, 1) void gemm_strip_kernel(GemmArgs a) {
 }
 
 // Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).
-// One wavefront per row; resid / out are row-major or fragment-major (see frag_offset_bytes); when inv_rms is given it
-// also leaves rsqrt(mean(out[m,:]^2) + eps) of the stored row there.
+// resid / out are row-major or fragment-major (see frag_offset_bytes); when inv_rms is given it also leaves
+// rsqrt(mean(out[m,:]^2) + eps) of the stored row there.  WPR wavefronts share a row: 1 (a workgroup covers 4 rows), or 4
+// (one row per workgroup, for calls of few rows, which would otherwise occupy a fraction of the chip).
+template <int WPR>
 __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float* __restrict__ partial, int splits,
                                                                      const bf16* __restrict__ resid, int ldr, int resid_frag,
                                                                      bf16* __restrict__ out, int ldo, int out_frag, int M, int N,
                                                                      float* __restrict__ inv_rms, float eps) {
+    static_assert(WPR == 1 || WPR == 4, "wavefronts per row");
     const int lane = threadIdx.x & 63;
-    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (m >= M) return;
+    const int wave = threadIdx.x >> 6;
+    const int m = WPR == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
+    const int col = WPR == 1 ? lane : wave * WAVE + lane;   // this lane's place among the WPR * 64 lanes of the row
+    constexpr int ROW_LANES = WPR * WAVE;
+    if (m >= M) return;  // (uniform for the workgroup when the wavefronts share a row)
     float ss = 0.0f;
     // four column groups per pass: all their loads are issued before the first sum (the kernel is one pass over
     // (4 splits + 4) N bytes per row; what it has to hide is latency)
     constexpr int G = 4;
-    for (int n0 = lane * 4; n0 < N; n0 += G * WAVE * 4) {
+    for (int n0 = col * 4; n0 < N; n0 += G * ROW_LANES * 4) {
         bf16x4 r4[G];
         f32x4 p[G][4];  // at most 4 planes
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int n = n0 + g * WAVE * 4;
+            const int n = n0 + g * ROW_LANES * 4;
             if (n < N) {
                 const size_t roff = resid_frag ? frag_offset_bytes(m, n, ldr) : ((size_t)m * ldr + n) * 2;
                 r4[g] = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const char*>(resid) + roff);
@@ -549,7 +598,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float
         }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int n = n0 + g * WAVE * 4;
+            const int n = n0 + g * ROW_LANES * 4;
             if (n < N) {
                 float v[4] = {bf16_to_f32(r4[g][0]), bf16_to_f32(r4[g][1]), bf16_to_f32(r4[g][2]), bf16_to_f32(r4[g][3])};
 #pragma unroll
@@ -570,6 +619,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_residual_kernel(const float
     }
     if (inv_rms != nullptr) {
         ss = wave_sum(ss);
-        if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)N + eps);
+        if constexpr (WPR == 1) {
+            if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)N + eps);
+        } else {
+            __shared__ float part[WPR];
+            if (lane == 0) part[wave] = ss;
+            __syncthreads();
+            if (threadIdx.x == 0) inv_rms[m] = rsqrtf((part[0] + part[1] + part[2] + part[3]) / (float)N + eps);
+        }
     }
 }

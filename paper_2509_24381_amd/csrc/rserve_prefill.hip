@@ -81,6 +81,8 @@ struct rs_ctx {
     int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
     int attn_variant = 1;     // RS_ATTN environment variable: 2 the wide software-pipelined attention kernel (256 rows per
                               // workgroup), 1 the 128-row software-pipelined one, 0 the plain one
+    int gemm_narrow = 1;      // RS_NARROW environment variable: 0 never uses the narrow GEMM geometry; otherwise launches of at most
+    int narrow_max_tiles_m = 1;  // narrow_max_tiles_m (RS_NARROW_TM) token blocks whose strips would hold at most 2 units use it
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
     // measurement hook: HIP events around every launch of one step of the layer
@@ -189,6 +191,14 @@ int strips_for(const rs_ctx* c, int tiles_m, int splits, int units) {
     return std::max(1, std::min(units, c->n_cu / std::max(1, tiles_m * splits)));
 }
 
+// Whether a launch qualifies for the narrow kernel geometry: few token blocks, no strip wider than the narrow tile.
+int narrow_strips_for(const rs_ctx* c, int tiles_m, int splits, int units) { return strips_for(c, tiles_m, splits, units); }
+bool use_narrow(const rs_ctx* c, int tiles_m, int splits, int units) {
+    if (!c->gemm_narrow || tiles_m > c->narrow_max_tiles_m) return false;
+    const int strips = narrow_strips_for(c, tiles_m, splits, units);
+    return (units + strips - 1) / strips <= GS_NARROW_NT;
+}
+
 // Estimated duration (shader clocks) of a residual GEMM cut into `splits` K ranges.  Constants fitted to measurements
 // on MI355X: a step of K = 64 costs 256 clocks of matrix-pipe issue per unit plus about 350 of barrier and issue overhead,
 // a tile about 20000 for pipeline fill and epilogue, and the reduction kernel moves its bytes at about 2 TB/s.
@@ -257,12 +267,20 @@ size_t fp8_expansion_bytes(const rs_ctx* c, long n_tokens) {
 template <int EPI>
 rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     a.tiles_m = (a.M + GS_BM - 1) / GS_BM;
-    a.strips = strips_for(c, a.tiles_m, splits, a.N / 32);
+    const int units = a.N / 32;
     const int steps = a.K / GS_BK;
     a.steps_per_split = (steps + splits - 1) / splits;
     splits = (steps + a.steps_per_split - 1) / a.steps_per_split;  // no empty K range
-    dim3 grid(a.tiles_m * a.strips, splits);
-    hipLaunchKernelGGL(gemm_strip_kernel<EPI>, grid, dim3(256), GS_LDS_BYTES, st, a);
+    if (use_narrow(c, a.tiles_m, splits, units)) {
+        a.strips = narrow_strips_for(c, a.tiles_m, splits, units);
+        dim3 grid(a.tiles_m * a.strips, splits);
+        hipLaunchKernelGGL((gemm_strip_kernel<EPI, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>), grid, dim3(256),
+                           GS_NARROW_LDS_BYTES, st, a);
+    } else {
+        a.strips = strips_for(c, a.tiles_m, splits, units);
+        dim3 grid(a.tiles_m * a.strips, splits);
+        hipLaunchKernelGGL(gemm_strip_kernel<EPI>, grid, dim3(256), GS_LDS_BYTES, st, a);
+    }
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -293,8 +311,12 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf1
     }
     rs_status s = launch_gemm<EPI_PARTIAL>(c, a, splits, st);
     if (s != RS_OK) return s;
-    hipLaunchKernelGGL(splitk_reduce_residual_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)partial, splits, resid, N,
-                       resid_frag, out, N, out_frag, M, N, inv_rms_out, eps);
+    if (M <= 512)  // few rows: a workgroup per row instead of per four
+        hipLaunchKernelGGL(splitk_reduce_residual_kernel<4>, dim3(M), dim3(256), 0, st, (const float*)partial, splits, resid, N,
+                           resid_frag, out, N, out_frag, M, N, inv_rms_out, eps);
+    else
+        hipLaunchKernelGGL(splitk_reduce_residual_kernel<1>, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)partial, splits, resid, N,
+                           resid_frag, out, N, out_frag, M, N, inv_rms_out, eps);
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
@@ -767,6 +789,8 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->mrope_b0 = c->mrope_b1 = f.head_dim / 2;  // 1-D RoPE: every pair turns with the first axis
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
     if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
+    if (const char* e = getenv("RS_NARROW")) c->gemm_narrow = atoi(e);
+    if (const char* e = getenv("RS_NARROW_TM")) c->narrow_max_tiles_m = atoi(e);
     if (const char* e = getenv("RS_ATTN_SPLIT")) c->attn_split = std::max(0, std::min(atoi(e), ATT_MAX_PARTS));
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
@@ -815,6 +839,10 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_QKV_ROPE, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)lm_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LM_ROWS * f.hidden * 4);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);

@@ -85,6 +85,12 @@ def test_sizes_and_kv_bookkeeping(lib):
     assert ctx.kv_bytes(0, 100) == 0
     assert ctx.workspace_bytes(128, 4) >= 128 * (256 + 512 + 256 + 1024) * 2
     assert ctx.workspace_bytes(128, 4) >= ctx.workspace_bytes(64, 2)
+    # a workspace sized for the largest call serves every smaller one: monotone in both arguments
+    sizes = [ctx.workspace_bytes(t, 1) for t in range(1, 129)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:]))
+    big = Context(tiny_cfg(max_tokens_per_call=1024))
+    sizes = [big.workspace_bytes(t, 2) for t in (1, 30, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 300, 512, 1000, 1024)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:]))
     assert ctx.weights_packed_bytes() >= 2 * (512 * 256 + 256 * 256 + 3 * 256 * 1024)
     kv = make_kv(lib, ctx)
     assert kv.capacity == 128 and kv.length(0) == 0 and kv.length(1) == 0
