@@ -71,8 +71,10 @@ constexpr int GS_BK = 64;                            // K per pipeline step
 // look-ahead), token fragments loaded one step ahead, one workgroup per compute unit with up to 512 registers per lane.
 // Narrow, for launches whose strips hold at most 2 units (few token rows spread over the whole chip): a step is then only
 // 8 or 16 MFMAs per wavefront, shorter than the memory latency one step of look-ahead would have to cover, so the ring has
-// 8 slots of 8 KB (seven steps of weight look-ahead), the token fragments are loaded three steps ahead (the accumulators
-// leave the registers for that), and two workgroups share a compute unit.
+// 8 slots of 8 KB (seven steps of weight look-ahead) and the token fragments are loaded three steps ahead (the accumulators
+// leave the registers for that).  Both are built for one wavefront per SIMD (OCC = 1: 512 registers per lane); with the
+// budget of two per SIMD the narrow kernel spills its token fragments, and two workgroups per compute unit measured no
+// faster.
 constexpr int GS_MAX_NT = 8;                         // units per tile (wide)
 constexpr int GS_SLOTS = 4;
 constexpr int GS_NARROW_NT = 2;

@@ -192,10 +192,9 @@ int strips_for(const rs_ctx* c, int tiles_m, int splits, int units) {
 }
 
 // Whether a launch qualifies for the narrow kernel geometry: few token blocks, no strip wider than the narrow tile.
-int narrow_strips_for(const rs_ctx* c, int tiles_m, int splits, int units) { return strips_for(c, tiles_m, splits, units); }
 bool use_narrow(const rs_ctx* c, int tiles_m, int splits, int units) {
     if (!c->gemm_narrow || tiles_m > c->narrow_max_tiles_m) return false;
-    const int strips = narrow_strips_for(c, tiles_m, splits, units);
+    const int strips = strips_for(c, tiles_m, splits, units);
     return (units + strips - 1) / strips <= GS_NARROW_NT;
 }
 
@@ -271,16 +270,13 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     const int steps = a.K / GS_BK;
     a.steps_per_split = (steps + splits - 1) / splits;
     splits = (steps + a.steps_per_split - 1) / a.steps_per_split;  // no empty K range
-    if (use_narrow(c, a.tiles_m, splits, units)) {
-        a.strips = narrow_strips_for(c, a.tiles_m, splits, units);
-        dim3 grid(a.tiles_m * a.strips, splits);
+    a.strips = strips_for(c, a.tiles_m, splits, units);
+    dim3 grid(a.tiles_m * a.strips, splits);
+    if (use_narrow(c, a.tiles_m, splits, units))
         hipLaunchKernelGGL((gemm_strip_kernel<EPI, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>), grid, dim3(256),
                            GS_NARROW_LDS_BYTES, st, a);
-    } else {
-        a.strips = strips_for(c, a.tiles_m, splits, units);
-        dim3 grid(a.tiles_m * a.strips, splits);
+    else
         hipLaunchKernelGGL(gemm_strip_kernel<EPI>, grid, dim3(256), GS_LDS_BYTES, st, a);
-    }
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
