@@ -77,16 +77,13 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the layer (extra passes)")
     ap.add_argument("--paged", action="store_true", help="keep the KV caches in pages of 64 tokens taken from one pool")
     ap.add_argument("--fp8-kv", action="store_true",
-                    help="keep the KV caches as E4M3 bytes (scale 1/8), expanded per call for attention; not with --paged")
+                    help="keep the KV caches as E4M3 bytes (scale 1/8), expanded per call for attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline sample is sized for")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain 256 MiB elementwise copy kernel (torch.mul(a, 1, out=b)); "
                          "gives the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs a kernel of known traffic to scale by")
     args = ap.parse_args()
-    if args.paged and args.fp8_kv:
-        print("bench.py: --paged and --fp8-kv exclude each other (8-bit caches are contiguous)", file=sys.stderr)
-        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -113,9 +110,9 @@ def main():
         stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=len(reqs), max_pos=wl.max_prior + wl.budget,
                                   fp8_visible_tokens=visible)
         kvs = []
-        pool = stack.new_pool(sum((r.prior_len + r.rows.shape[0] + 63) // 64 for r in reqs)) if args.paged else None
+        pool = stack.new_pool(sum((r.prior_len + r.rows.shape[0] + 63) // 64 for r in reqs), fp8=args.fp8_kv) if args.paged else None
         for r in reqs:
-            kv = (pool.new_cache(1) if args.paged else
+            kv = (pool.new_cache(1, 0.125, 0.125) if args.paged else
                   stack.new_cache_fp8(wl.max_prior + wl.budget, 0.125, 0.125) if args.fp8_kv else
                   stack.new_cache(wl.max_prior + wl.budget))
             if r.prior_len:
@@ -135,8 +132,8 @@ def main():
         chunks = wl.chunks()
         stack = runner.LayerStack(sh, weights, max_tokens=wl.budget, max_requests=1, max_pos=wl.n_tokens,
                                   fp8_visible_tokens=wl.n_tokens if args.fp8_kv else 0)
-        pool = stack.new_pool(wl.n_layers * ((wl.n_tokens + 63) // 64)) if args.paged else None
-        kv = (pool.new_cache(wl.n_layers) if args.paged else
+        pool = stack.new_pool(wl.n_layers * ((wl.n_tokens + 63) // 64), fp8=args.fp8_kv) if args.paged else None
+        kv = (pool.new_cache(wl.n_layers, 0.125, 0.125) if args.paged else
               stack.new_cache_fp8(wl.n_tokens, 0.125, 0.125) if args.fp8_kv else stack.new_cache(wl.n_tokens))
         x_dev = runner.to_device_bf16(x)
         call_shapes = [(b - a, a) for a, b in chunks]
@@ -184,8 +181,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.n_layers, "tokens_per_step": n_tokens, "token_budget": wl.budget,
-                   "calls_per_step": calls_per_step, "kv_cache": "paged (64-token pages)" if args.paged else
-                               "8-bit E4M3, contiguous" if args.fp8_kv else "contiguous",
+                   "calls_per_step": calls_per_step, "kv_cache": ("8-bit E4M3, " if args.fp8_kv else "") + ("paged (64-token pages)" if args.paged else "contiguous"),
                    "shape": f"hidden {sh.hidden}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, head_dim {sh.head_dim}, "
                             f"mlp {sh.mlp_inter}"},
         "tflops": tflops,

@@ -158,7 +158,12 @@ size_t rs_workspace_bytes(const rs_ctx* ctx, int max_tokens, int max_requests);
  * model).  Queries, scores and everything else stay as with a bfloat16 cache.
  *   rs_kv_fp8_bytes    bytes of device memory for n_layers layers of capacity_tokens tokens (half of rs_kv_bytes).
  *   rs_kv_alloc_fp8    like rs_kv_alloc; k_scale, v_scale > 0 and finite, with finite reciprocals (RS_EINVAL otherwise).
- *                      Contiguous only: there is no paged 8-bit cache.
+ *   rs_kv_page_bytes_fp8, rs_kv_pool_create_fp8, rs_kv_alloc_paged_fp8   the paged form: a pool of 8-bit pages (half of
+ *                      rs_kv_page_bytes: 64 tokens of one layer, K then V^T codes of all KV heads) and growable caches on
+ *                      it, with everything said above about pools and paged caches.  A pool serves one kind of cache:
+ *                      rs_kv_alloc_paged on an 8-bit pool, or rs_kv_alloc_paged_fp8 on a bfloat16 one, is RS_ESTATE.
+ *                      Results are bit-identical to those with a contiguous 8-bit cache.
+ *   rs_kv_pool_is_fp8  1 / 0, -1 for a null handle.
  *   rs_kv_is_fp8       1 / 0, -1 for a null handle.
  *   rs_kv_export / rs_kv_import on an 8-bit cache produce / consume bfloat16 rows through the formulas above.
  *   rs_kv_export_codes, rs_kv_import_codes   the bytes themselves, canonical [len][Hkv][d] uint8 device arrays: what a
@@ -177,6 +182,10 @@ rs_status rs_kv_export_codes(const rs_kv* kv, int layer, void* k_codes_dev, void
 rs_status rs_kv_import_codes(rs_kv* kv, int layer, const void* k_codes_dev, const void* v_codes_dev, int n_tokens,
                              void* hip_stream);
 size_t rs_workspace_bytes_fp8kv(const rs_ctx* ctx, int max_tokens, int max_requests, size_t max_visible_tokens);
+size_t rs_kv_page_bytes_fp8(const rs_ctx* ctx);
+rs_status rs_kv_pool_create_fp8(rs_ctx* ctx, void* dev_mem, size_t bytes, rs_kv_pool** out);
+int rs_kv_pool_is_fp8(const rs_kv_pool* pool);
+rs_status rs_kv_alloc_paged_fp8(rs_ctx* ctx, rs_kv_pool* pool, int n_layers, float k_scale, float v_scale, rs_kv** out);
 
 /* One chunk of one request through one layer (chunked prefill, section 2.2.1).
  *   x   device bf16 [T, H]: the chunk's rows (image-embedding or text-embedding rows alike), prompt order.

@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "rs_kv_page_bytes", "rs_kv_pool_create", "rs_kv_pool_destroy", "rs_kv_pool_pages", "rs_kv_pool_free_pages",
     "rs_kv_alloc_paged",
     "rs_kv_fp8_bytes", "rs_kv_alloc_fp8", "rs_kv_is_fp8", "rs_kv_export_codes", "rs_kv_import_codes", "rs_workspace_bytes_fp8kv",
+    "rs_kv_page_bytes_fp8", "rs_kv_pool_create_fp8", "rs_kv_pool_is_fp8", "rs_kv_alloc_paged_fp8",
     "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
@@ -113,6 +114,10 @@ def load_library():
         "rs_kv_export_codes": (i, [vp, i, vp, vp, vp]),
         "rs_kv_import_codes": (i, [vp, i, vp, vp, i, vp]),
         "rs_workspace_bytes_fp8kv": (sz, [vp, i, i, sz]),
+        "rs_kv_page_bytes_fp8": (sz, [vp]),
+        "rs_kv_pool_create_fp8": (i, [vp, vp, sz, C.POINTER(vp)]),
+        "rs_kv_pool_is_fp8": (i, [vp]),
+        "rs_kv_alloc_paged_fp8": (i, [vp, vp, i, C.c_float, C.c_float, C.POINTER(vp)]),
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
@@ -196,13 +201,15 @@ class PackedWeights:
 class KVPool:
     """A pool of KV pages (64 tokens of one layer each) in one device slab; paged caches take their pages from it."""
 
-    def __init__(self, ctx: "Context", n_pages: int):
+    def __init__(self, ctx: "Context", n_pages: int, fp8: bool = False):
         import torch
         self.ctx = ctx
-        self.page_bytes = ctx.lib.rs_kv_page_bytes(ctx.handle)
+        self.fp8 = fp8
+        self.page_bytes = (ctx.lib.rs_kv_page_bytes_fp8 if fp8 else ctx.lib.rs_kv_page_bytes)(ctx.handle)
         self.slab = torch.empty(max(n_pages * self.page_bytes, 256), dtype=torch.uint8, device="cuda")
         h = C.c_void_p()
-        _check(ctx.lib.rs_kv_pool_create(ctx.handle, _ptr(self.slab), n_pages * self.page_bytes, C.byref(h)))
+        create = ctx.lib.rs_kv_pool_create_fp8 if fp8 else ctx.lib.rs_kv_pool_create
+        _check(create(ctx.handle, _ptr(self.slab), n_pages * self.page_bytes, C.byref(h)))
         self.handle = h
 
     def __del__(self):
@@ -221,9 +228,13 @@ class KVPool:
     def free_pages(self) -> int:
         return load_library().rs_kv_pool_free_pages(self.handle)
 
-    def new_cache(self, n_layers: int) -> "KVCache":
+    def new_cache(self, n_layers: int, k_scale: float = 1.0, v_scale: float = 1.0) -> "KVCache":
+        """An empty growable cache on this pool (the scales matter for a pool of 8-bit pages only)."""
         h = C.c_void_p()
-        _check(self.ctx.lib.rs_kv_alloc_paged(self.ctx.handle, self.handle, n_layers, C.byref(h)))
+        if self.fp8:
+            _check(self.ctx.lib.rs_kv_alloc_paged_fp8(self.ctx.handle, self.handle, n_layers, k_scale, v_scale, C.byref(h)))
+        else:
+            _check(self.ctx.lib.rs_kv_alloc_paged(self.ctx.handle, self.handle, n_layers, C.byref(h)))
         return KVCache(self.ctx, h.value, self.slab, pool=self)
 
 

@@ -5,7 +5,7 @@
 //   read    value = bf16( fl32( decode(code) * scale ) )
 //
 // The cache keeps the tile layout of the bfloat16 one with one byte per element: per KV head, K tiles [64 tokens][d]
-// and V^T tiles [d][64 tokens].  The attention kernels do not read it: before attention, the blocks a call's rows can see
+// and V^T tiles [d][64 tokens], contiguous per layer or in pages of 64 tokens.  The attention kernels do not read it: before attention, the blocks a call's rows can see
 // are expanded to bfloat16 tiles in the call's workspace (one layer's worth, reused by every layer), which the unchanged
 // attention kernel then walks.  Expanding costs one pass over the prefix at HBM speed (a few microseconds per 10k
 // tokens), far less than converting inside the attention loop, whose limit is LDS bandwidth and issue slots, not HBM.
@@ -17,10 +17,13 @@
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 struct Fp8CacheDesc {
-    uint8_t* kc;   // K codes of the layer: [Hkv][cap/64][64][d]
-    uint8_t* vc;   // V^T codes of the layer: [Hkv][cap/64][d][64]
-    int cap;       // capacity of the 8-bit cache in tokens (multiple of 64)
+    uint8_t* kc;   // contiguous: K codes of the layer, [Hkv][cap/64][64][d];  paged: the pool's base
+    uint8_t* vc;   // contiguous: V^T codes of the layer, [Hkv][cap/64][d][64];  paged: unused
+    const int* pages;  // paged: page number of each 64-token block of this layer (device memory); null for a contiguous cache
+    int cap;       // contiguous: capacity in tokens (multiple of 64)
     int xb0;       // number of the request's first block among the blocks the call expands
+    int hkv;       // KV heads (a page holds their K tiles, then their V^T tiles)
+    int pad_;
     float k_inv, v_inv;      // fl32(1 / scale)
     float k_scale, v_scale;
 };
@@ -68,6 +71,13 @@ RS_DEVICE uint8_t e4m3_from_bf16(bf16 v, float inv) { return (uint8_t)(e4m3_pair
 
 RS_DEVICE size_t fp8_tile_offset(int cap, int c, int block, int D) { return ((size_t)c * (size_t)(cap >> 6) + (size_t)block) * 64 * D; }
 
+// The K (v = false) or V^T (v = true) tile of KV head c and 64-token block `block` of an 8-bit cache.  A page of a paged
+// cache holds 64 tokens of one layer: the K tiles of all KV heads, then their V^T tiles, 64 d bytes each.
+RS_DEVICE uint8_t* fp8_tile(const Fp8CacheDesc& fc, bool v, int c, int block, int D) {
+    if (fc.pages == nullptr) return (v ? fc.vc : fc.kc) + fp8_tile_offset(fc.cap, c, block, D);
+    return fc.kc + ((size_t)fc.pages[block] * 2 * fc.hkv + (size_t)(v ? fc.hkv : 0) + (size_t)c) * 64 * D;
+}
+
 // ---------------------------------------------------------------- append
 // One workgroup per (touched 64-token block, KV head), as in append_kv_kernel: the rotated k rows and the v rows of the
 // call are quantised into the request's 8-bit cache.  Tokens before P keep their codes; V codes at or beyond P + T inside
@@ -86,8 +96,8 @@ __global__ __launch_bounds__(256) void append_kv_fp8_kernel(const bf16* __restri
     const int k_col = (Hq + c) * D;
     const int v_col = (Hq + Hkv + c) * D;
     constexpr int CPR = D / 8;  // chunks of 8 elements per row
-    uint8_t* const k_tile = fc.kc + fp8_tile_offset(fc.cap, c, it.block, D);
-    uint8_t* const v_tile = fc.vc + fp8_tile_offset(fc.cap, c, it.block, D);
+    uint8_t* const k_tile = fp8_tile(fc, false, c, it.block, D);
+    uint8_t* const v_tile = fp8_tile(fc, true, c, it.block, D);
     for (int idx = threadIdx.x; idx < 64 * CPR; idx += blockDim.x) {
         const int kk = idx / CPR, ch = idx - kk * CPR;
         const int pos = tok0 + kk;
@@ -136,8 +146,8 @@ __global__ __launch_bounds__(256) void kv_expand_fp8_kernel(const ReqDesc* __res
     const int c = blockIdx.y;
     const int tok0 = block * 64;
     const int end = rq.P + rq.T;
-    const uint8_t* k_src = fc.kc + fp8_tile_offset(fc.cap, c, block, D);
-    const uint8_t* v_src = fc.vc + fp8_tile_offset(fc.cap, c, block, D);
+    const uint8_t* k_src = fp8_tile(fc, false, c, block, D);
+    const uint8_t* v_src = fp8_tile(fc, true, c, block, D);
     bf16* k_dst = rq.kcache + fp8_tile_offset(rq.cap, c, block, D);
     bf16* v_dst = rq.vtcache + fp8_tile_offset(rq.cap, c, block, D);
     constexpr int CPR = D / 16;  // chunks of 16 codes per K row
@@ -177,50 +187,59 @@ __global__ __launch_bounds__(256) void kv_expand_fp8_kernel(const ReqDesc* __res
 }
 
 // ---------------------------------------------------------------- export / import (canonical [tokens][Hkv][d])
-// Tokens [0, n) of one layer.  With code outputs (inputs) given the bytes travel as they are; otherwise the bfloat16
-// values are produced (consumed) through the read (store) formula above.
+// Tokens [t0, t0 + n) of one layer, t0 a multiple of 64.  The cache is described by an Fp8CacheDesc whose `pages` is only a
+// marker here (non-null: paged): the page numbers of blocks [block0, block0 + KV_PAGE_WINDOW) ride in the kernel
+// arguments, as for the bfloat16 caches.  With code outputs (inputs) given the bytes travel as they are; otherwise the
+// bfloat16 values are produced (consumed) through the read (store) formula above.
 template <int D>
-__global__ __launch_bounds__(256) void kv_fp8_export_kernel(const uint8_t* __restrict__ kc, const uint8_t* __restrict__ vc, int cap,
-                                                            int Hkv, float k_scale, float v_scale, bf16* __restrict__ k_out,
+RS_DEVICE uint8_t* fp8_window_tile(const Fp8CacheDesc& fc, const KVPageWindow& win, int block0, bool v, int c, int block) {
+    if (fc.pages == nullptr) return (v ? fc.vc : fc.kc) + fp8_tile_offset(fc.cap, c, block, D);
+    return fc.kc + ((size_t)win.page[block - block0] * 2 * fc.hkv + (size_t)(v ? fc.hkv : 0) + (size_t)c) * 64 * D;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_fp8_export_kernel(Fp8CacheDesc fc, KVPageWindow win, int block0, bf16* __restrict__ k_out,
                                                             bf16* __restrict__ v_out, uint8_t* __restrict__ kc_out,
-                                                            uint8_t* __restrict__ vc_out, int n) {
+                                                            uint8_t* __restrict__ vc_out, int t0, int n) {
+    const int Hkv = fc.hkv;
     const size_t total = (size_t)n * Hkv * D;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int dd = (int)(i % D);
         const int c = (int)((i / D) % Hkv);
-        const int t = (int)(i / ((size_t)D * Hkv));
-        const size_t tile = fp8_tile_offset(cap, c, t >> 6, D);
-        const uint8_t ck = kc[tile + (size_t)(t & 63) * D + dd];
-        const uint8_t cv = vc[tile + (size_t)dd * 64 + (t & 63)];
+        const int t = t0 + (int)(i / ((size_t)D * Hkv));
+        const size_t o = (size_t)t0 * Hkv * D + i;
+        const uint8_t ck = fp8_window_tile<D>(fc, win, block0, false, c, t >> 6)[(size_t)(t & 63) * D + dd];
+        const uint8_t cv = fp8_window_tile<D>(fc, win, block0, true, c, t >> 6)[(size_t)dd * 64 + (t & 63)];
         if (kc_out) {
-            kc_out[i] = ck;
-            vc_out[i] = cv;
+            kc_out[o] = ck;
+            vc_out[o] = cv;
         } else {
-            k_out[i] = bf16_from_e4m3(ck, k_scale);
-            v_out[i] = bf16_from_e4m3(cv, v_scale);
+            k_out[o] = bf16_from_e4m3(ck, fc.k_scale);
+            v_out[o] = bf16_from_e4m3(cv, fc.v_scale);
         }
     }
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void kv_fp8_import_kernel(uint8_t* __restrict__ kc, uint8_t* __restrict__ vc, int cap, int Hkv,
-                                                            float k_inv, float v_inv, const bf16* __restrict__ k_in,
+__global__ __launch_bounds__(256) void kv_fp8_import_kernel(Fp8CacheDesc fc, KVPageWindow win, int block0, const bf16* __restrict__ k_in,
                                                             const bf16* __restrict__ v_in, const uint8_t* __restrict__ kc_in,
-                                                            const uint8_t* __restrict__ vc_in, int n) {
-    const int n_pad = (n + 63) & ~63;  // the last touched V block is zero beyond n
+                                                            const uint8_t* __restrict__ vc_in, int t0, int n) {
+    const int Hkv = fc.hkv;
+    const int n_pad = (n + 63) & ~63;  // the last touched V block is zero beyond t0 + n
     const size_t total = (size_t)n_pad * Hkv * D;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int dd = (int)(i % D);
         const int c = (int)((i / D) % Hkv);
-        const int t = (int)(i / ((size_t)D * Hkv));
-        const bool live = t < n;
-        const size_t tile = fp8_tile_offset(cap, c, t >> 6, D);
-        uint8_t ck = 0, cv = 0;
+        const int tl = (int)(i / ((size_t)D * Hkv));
+        const int t = t0 + tl;
+        const bool live = tl < n;
+        const size_t o = (size_t)t0 * Hkv * D + i;
+        uint8_t cv = 0;
         if (live) {
-            ck = kc_in ? kc_in[i] : e4m3_from_bf16(k_in[i], k_inv);
-            cv = vc_in ? vc_in[i] : e4m3_from_bf16(v_in[i], v_inv);
-            kc[tile + (size_t)(t & 63) * D + dd] = ck;
+            const uint8_t ck = kc_in ? kc_in[o] : e4m3_from_bf16(k_in[o], fc.k_inv);
+            cv = vc_in ? vc_in[o] : e4m3_from_bf16(v_in[o], fc.v_inv);
+            fp8_window_tile<D>(fc, win, block0, false, c, t >> 6)[(size_t)(t & 63) * D + dd] = ck;
         }
-        vc[tile + (size_t)dd * 64 + (t & 63)] = cv;
+        fp8_window_tile<D>(fc, win, block0, true, c, t >> 6)[(size_t)dd * 64 + (t & 63)] = cv;
     }
 }

@@ -101,6 +101,7 @@ struct rs_kv_pool {
     char* base;
     size_t page_bytes;
     int n_pages;
+    bool fp8 = false;              // pages of E4M3 bytes (half the size) for 8-bit caches
     int n_caches = 0;              // paged caches alive on this pool
     std::vector<int> free_pages;   // stack: the back is handed out next
 };
@@ -376,36 +377,72 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     return RS_OK;
 }
 
+// Runs an 8-bit cache's export or import kernel over tokens [0, n): in one launch for a contiguous cache, in windows of
+// KV_PAGE_WINDOW blocks (whose page numbers ride in the kernel arguments) for a paged one.
+template <class Launch>
+void for_each_fp8_window(const rs_kv* kv, int layer, int n, Launch&& launch) {
+    Fp8CacheDesc fc{};
+    fc.hkv = kv->ctx->cfg.n_kv_heads;
+    fc.k_scale = kv->k_scale; fc.v_scale = kv->v_scale;
+    fc.k_inv = 1.0f / kv->k_scale; fc.v_inv = 1.0f / kv->v_scale;
+    KVPageWindow win{};
+    if (!kv->paged()) {
+        fc.kc = kv->kc_of(layer); fc.vc = kv->vc_of(layer); fc.cap = kv->cap;
+        launch(fc, win, 0, 0, n);
+        return;
+    }
+    fc.kc = reinterpret_cast<uint8_t*>(kv->pool->base);
+    fc.pages = reinterpret_cast<const int*>(kv->pool->base);   // non-null marker: the numbers come from the window
+    const int window_tokens = KV_PAGE_WINDOW * 64;
+    for (int t0 = 0; t0 < n; t0 += window_tokens) {
+        const int nt = std::min(window_tokens, n - t0);
+        const int b0 = t0 / 64, nb = (nt + 63) / 64;
+        for (int b = 0; b < nb; ++b) win.page[b] = kv->pages[layer][b0 + b];
+        launch(fc, win, b0, t0, nt);
+    }
+}
+
 // Tokens [0, len) of an 8-bit cache's layer as bfloat16 values or as codes (whichever pair of outputs is given).
 rs_status fp8_export(const rs_kv* kv, int layer, bf16* k_out, bf16* v_out, uint8_t* kc_out, uint8_t* vc_out, hipStream_t st) {
-    const int n = kv->len[layer];
-    const size_t total = (size_t)n * kv->ctx->kv_dim;
-    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-    const int hkv = kv->ctx->cfg.n_kv_heads;
-    if (kv->ctx->cfg.head_dim == 128)
-        hipLaunchKernelGGL(kv_fp8_export_kernel<128>, dim3(blocks), dim3(256), 0, st, (const uint8_t*)kv->kc_of(layer),
-                           (const uint8_t*)kv->vc_of(layer), kv->cap, hkv, kv->k_scale, kv->v_scale, k_out, v_out, kc_out, vc_out, n);
-    else
-        hipLaunchKernelGGL(kv_fp8_export_kernel<64>, dim3(blocks), dim3(256), 0, st, (const uint8_t*)kv->kc_of(layer),
-                           (const uint8_t*)kv->vc_of(layer), kv->cap, hkv, kv->k_scale, kv->v_scale, k_out, v_out, kc_out, vc_out, n);
+    const int kv_dim = kv->ctx->kv_dim;
+    const bool d128 = kv->ctx->cfg.head_dim == 128;
+    for_each_fp8_window(kv, layer, kv->len[layer], [&](const Fp8CacheDesc& fc, const KVPageWindow& win, int b0, int t0, int nt) {
+        const int blocks = (int)std::min<size_t>(((size_t)nt * kv_dim + 255) / 256, 4096);
+        if (d128)
+            hipLaunchKernelGGL(kv_fp8_export_kernel<128>, dim3(blocks), dim3(256), 0, st, fc, win, b0, k_out, v_out, kc_out, vc_out, t0, nt);
+        else
+            hipLaunchKernelGGL(kv_fp8_export_kernel<64>, dim3(blocks), dim3(256), 0, st, fc, win, b0, k_out, v_out, kc_out, vc_out, t0, nt);
+    });
     RS_HIP(hipGetLastError());
     return RS_OK;
 }
 
-// Fills tokens [0, n) of an 8-bit cache's layer from bfloat16 values or from codes (the caller has checked n against cap).
+// Fills tokens [0, n) of an 8-bit cache's layer from bfloat16 values or from codes (the caller has checked n against the
+// capacity and, for a paged cache, taken the pages).
 rs_status fp8_import(rs_kv* kv, int layer, const bf16* k_in, const bf16* v_in, const uint8_t* kc_in, const uint8_t* vc_in, int n,
                      hipStream_t st) {
-    const size_t total = align_up((size_t)n, 64) * kv->ctx->kv_dim;
-    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
-    const int hkv = kv->ctx->cfg.n_kv_heads;
-    const float k_inv = 1.0f / kv->k_scale, v_inv = 1.0f / kv->v_scale;
-    if (kv->ctx->cfg.head_dim == 128)
-        hipLaunchKernelGGL(kv_fp8_import_kernel<128>, dim3(blocks), dim3(256), 0, st, kv->kc_of(layer), kv->vc_of(layer), kv->cap, hkv,
-                           k_inv, v_inv, k_in, v_in, kc_in, vc_in, n);
-    else
-        hipLaunchKernelGGL(kv_fp8_import_kernel<64>, dim3(blocks), dim3(256), 0, st, kv->kc_of(layer), kv->vc_of(layer), kv->cap, hkv,
-                           k_inv, v_inv, k_in, v_in, kc_in, vc_in, n);
+    const int kv_dim = kv->ctx->kv_dim;
+    const bool d128 = kv->ctx->cfg.head_dim == 128;
+    for_each_fp8_window(kv, layer, n, [&](const Fp8CacheDesc& fc, const KVPageWindow& win, int b0, int t0, int nt) {
+        const int blocks = (int)std::min<size_t>((align_up((size_t)nt, 64) * kv_dim + 255) / 256, 4096);
+        if (d128)
+            hipLaunchKernelGGL(kv_fp8_import_kernel<128>, dim3(blocks), dim3(256), 0, st, fc, win, b0, k_in, v_in, kc_in, vc_in, t0, nt);
+        else
+            hipLaunchKernelGGL(kv_fp8_import_kernel<64>, dim3(blocks), dim3(256), 0, st, fc, win, b0, k_in, v_in, kc_in, vc_in, t0, nt);
+    });
     RS_HIP(hipGetLastError());
+    return RS_OK;
+}
+
+// The checks rs_kv_import and rs_kv_import_codes share, in the order they are reported; changes nothing.
+rs_status import_check(const rs_kv* kv, int layer, int n_tokens) {
+    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
+    if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
+    if (!kv->paged() && n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
+    if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
+    if (kv->paged() && kv->pages_missing(layer, n_tokens) > (int)kv->pool->free_pages.size())
+        return fail(RS_ECAPACITY, "the import needs %d new KV pages, the pool has %zu free", kv->pages_missing(layer, n_tokens),
+                    kv->pool->free_pages.size());
     return RS_OK;
 }
 
@@ -548,7 +585,14 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         d.row0 = row0; d.T = Ti; d.P = P;
         if (kv->fp8) {  // the kernels append to the 8-bit cache and attend to its expansion in the workspace
             Fp8CacheDesc fc{};
-            fc.kc = kv->kc_of(layer); fc.vc = kv->vc_of(layer); fc.cap = kv->cap; fc.xb0 = n_xblocks;
+            if (kv->paged()) {   // the 8-bit kernels look the pages up; attention reads the (contiguous) expansion
+                fc.kc = reinterpret_cast<uint8_t*>(kv->pool->base);
+                fc.pages = d.pages;
+                d.pages = nullptr;
+            } else {
+                fc.kc = kv->kc_of(layer); fc.vc = kv->vc_of(layer); fc.cap = kv->cap;
+            }
+            fc.xb0 = n_xblocks; fc.hkv = f.n_kv_heads;
             fc.k_scale = kv->k_scale; fc.v_scale = kv->v_scale;
             fc.k_inv = 1.0f / kv->k_scale; fc.v_inv = 1.0f / kv->v_scale;
             fp8s.push_back(fc);
@@ -713,10 +757,10 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     tm.end(RS_STEP_QKV_GEMM);
     // cache append, attention
     if (f.head_dim == 128)
-        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
+        s = launch_attention_path<128>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty() && fp8s.empty(),
                                        attn_split, d_mitems, (int)mitems.size(), d_fp8, (int)reqs.size(), n_xblocks, st, tm);
     else
-        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty(),
+        s = launch_attention_path<64>(ctx, qkv, attn, d_reqs, d_items, (int)items.size(), d_vb, (int)vbs.size(), !pagetab.empty() && fp8s.empty(),
                                       attn_split, d_mitems, (int)mitems.size(), d_fp8, (int)reqs.size(), n_xblocks, st, tm);
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
@@ -954,6 +998,11 @@ rs_status rs_kv_alloc(rs_ctx* c, int n_layers, int capacity_tokens, void* dev_me
     return RS_OK;
 }
 
+static bool fp8_scales_ok(float k_scale, float v_scale) {
+    return k_scale > 0.0f && v_scale > 0.0f && std::isfinite(k_scale) && std::isfinite(v_scale) && std::isfinite(1.0f / k_scale) &&
+           std::isfinite(1.0f / v_scale);
+}
+
 size_t rs_kv_fp8_bytes(const rs_ctx* c, int n_layers, int capacity_tokens) {
     if (!c || n_layers <= 0 || capacity_tokens <= 0) return 0;
     const size_t cap = align_up((size_t)capacity_tokens, 64);
@@ -966,8 +1015,7 @@ rs_status rs_kv_alloc_fp8(rs_ctx* c, int n_layers, int capacity_tokens, float k_
     if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
     *out = nullptr;
     if (n_layers <= 0 || capacity_tokens <= 0) return fail(RS_EINVAL, "n_layers and capacity_tokens must be positive");
-    if (!(k_scale > 0.0f) || !(v_scale > 0.0f) || !std::isfinite(k_scale) || !std::isfinite(v_scale) ||
-        !std::isfinite(1.0f / k_scale) || !std::isfinite(1.0f / v_scale))
+    if (!fp8_scales_ok(k_scale, v_scale))
         return fail(RS_EINVAL, "k_scale = %g and v_scale = %g must be positive, finite and have a finite reciprocal", k_scale, v_scale);
     if (!dev_mem || !aligned(dev_mem, 256)) return fail(RS_EINVAL, "dev_mem must be a 256-byte aligned device pointer");
     const size_t need = rs_kv_fp8_bytes(c, n_layers, capacity_tokens);
@@ -994,11 +1042,18 @@ size_t rs_kv_page_bytes(const rs_ctx* c) {
     return (size_t)2 * c->cfg.n_kv_heads * 64 * c->cfg.head_dim * 2;
 }
 
-rs_status rs_kv_pool_create(rs_ctx* c, void* dev_mem, size_t bytes, rs_kv_pool** out) {
+size_t rs_kv_page_bytes_fp8(const rs_ctx* c) { return rs_kv_page_bytes(c) / 2; }
+
+static rs_status pool_create(rs_ctx* c, void* dev_mem, size_t bytes, bool fp8, rs_kv_pool** out);
+rs_status rs_kv_pool_create(rs_ctx* c, void* dev_mem, size_t bytes, rs_kv_pool** out) { return pool_create(c, dev_mem, bytes, false, out); }
+rs_status rs_kv_pool_create_fp8(rs_ctx* c, void* dev_mem, size_t bytes, rs_kv_pool** out) { return pool_create(c, dev_mem, bytes, true, out); }
+int rs_kv_pool_is_fp8(const rs_kv_pool* p) { return p ? (p->fp8 ? 1 : 0) : -1; }
+
+static rs_status pool_create(rs_ctx* c, void* dev_mem, size_t bytes, bool fp8, rs_kv_pool** out) {
     if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
     *out = nullptr;
     if (!dev_mem || !aligned(dev_mem, 256)) return fail(RS_EINVAL, "dev_mem must be a 256-byte aligned device pointer");
-    const size_t pb = rs_kv_page_bytes(c);
+    const size_t pb = fp8 ? rs_kv_page_bytes_fp8(c) : rs_kv_page_bytes(c);
     const size_t n = bytes / pb;
     if (n == 0) return fail(RS_EWORKSPACE, "the pool's memory (%zu bytes) is smaller than one page (%zu bytes)", bytes, pb);
     if (n > (size_t)0x7fffffff) return fail(RS_EINVAL, "more than 2^31 - 1 pages");
@@ -1006,6 +1061,7 @@ rs_status rs_kv_pool_create(rs_ctx* c, void* dev_mem, size_t bytes, rs_kv_pool**
     p->ctx = c;
     p->base = reinterpret_cast<char*>(dev_mem);
     p->page_bytes = pb;
+    p->fp8 = fp8;
     p->n_pages = (int)n;
     p->free_pages.resize(n);
     for (size_t i = 0; i < n; ++i) p->free_pages[i] = (int)(n - 1 - i);  // page 0 is handed out first
@@ -1023,12 +1079,24 @@ rs_status rs_kv_pool_destroy(rs_kv_pool* p) {
 int rs_kv_pool_pages(const rs_kv_pool* p) { return p ? p->n_pages : -1; }
 int rs_kv_pool_free_pages(const rs_kv_pool* p) { return p ? (int)p->free_pages.size() : -1; }
 
+static rs_status alloc_paged(rs_ctx* c, rs_kv_pool* pool, int n_layers, bool fp8, float k_scale, float v_scale, rs_kv** out);
 rs_status rs_kv_alloc_paged(rs_ctx* c, rs_kv_pool* pool, int n_layers, rs_kv** out) {
+    return alloc_paged(c, pool, n_layers, false, 1.0f, 1.0f, out);
+}
+rs_status rs_kv_alloc_paged_fp8(rs_ctx* c, rs_kv_pool* pool, int n_layers, float k_scale, float v_scale, rs_kv** out) {
+    return alloc_paged(c, pool, n_layers, true, k_scale, v_scale, out);
+}
+
+static rs_status alloc_paged(rs_ctx* c, rs_kv_pool* pool, int n_layers, bool fp8, float k_scale, float v_scale, rs_kv** out) {
     if (!c || !out) return fail(RS_EINVAL, "ctx / out is null");
     *out = nullptr;
     if (!pool) return fail(RS_EINVAL, "pool is null");
     if (pool->ctx != c) return fail(RS_ESTATE, "the pool belongs to another context");
+    if (pool->fp8 != fp8)
+        return fail(RS_ESTATE, "the pool holds %s pages, the cache asked for is %s", pool->fp8 ? "8-bit" : "bfloat16", fp8 ? "8-bit" : "bfloat16");
     if (n_layers <= 0) return fail(RS_EINVAL, "n_layers must be positive");
+    if (fp8 && !fp8_scales_ok(k_scale, v_scale))
+        return fail(RS_EINVAL, "k_scale = %g and v_scale = %g must be positive, finite and have a finite reciprocal", k_scale, v_scale);
     rs_kv* kv = new rs_kv();
     kv->ctx = c;
     kv->n_layers = n_layers;
@@ -1037,6 +1105,9 @@ rs_status rs_kv_alloc_paged(rs_ctx* c, rs_kv_pool* pool, int n_layers, rs_kv** o
     kv->k_bytes = kv->layer_bytes = 0;
     kv->len.assign(n_layers, 0);
     kv->pool = pool;
+    kv->fp8 = fp8;
+    kv->k_scale = k_scale;
+    kv->v_scale = v_scale;
     kv->pages.assign(n_layers, std::vector<int>());
     ++pool->n_caches;
     *out = kv;
@@ -1107,13 +1178,10 @@ rs_status rs_kv_export(const rs_kv* kv, int layer, void* k_out, void* v_out, voi
 
 rs_status rs_kv_import(rs_kv* kv, int layer, const void* k, const void* v, int n_tokens, void* stream) {
     if (!kv) return fail(RS_EINVAL, "kv is null");
-    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
-    if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
-    if (!kv->paged() && n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
-    if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
-    if (kv->paged() && kv->pages_missing(layer, n_tokens) > (int)kv->pool->free_pages.size())
-        return fail(RS_ECAPACITY, "the import needs %d new KV pages, the pool has %zu free", kv->pages_missing(layer, n_tokens),
-                    kv->pool->free_pages.size());
+    {
+        const rs_status s = import_check(kv, layer, n_tokens);
+        if (s != RS_OK) return s;
+    }
     if (n_tokens == 0) {
         kv->len[layer] = 0;
         if (kv->paged()) kv->give_back_pages(layer, 0);
@@ -1159,16 +1227,21 @@ rs_status rs_kv_export_codes(const rs_kv* kv, int layer, void* k_codes, void* v_
 rs_status rs_kv_import_codes(rs_kv* kv, int layer, const void* k_codes, const void* v_codes, int n_tokens, void* stream) {
     if (!kv) return fail(RS_EINVAL, "kv is null");
     if (!kv->fp8) return fail(RS_ESTATE, "not an 8-bit cache");
-    if (layer < 0 || layer >= kv->n_layers) return fail(RS_EINVAL, "layer %d out of range", layer);
-    if (n_tokens < 0) return fail(RS_EINVAL, "n_tokens is negative");
-    if (n_tokens > kv->cap) return fail(RS_ECAPACITY, "%d tokens exceed cache capacity %d", n_tokens, kv->cap);
-    if (n_tokens > kv->ctx->cfg.max_pos) return fail(RS_ECAPACITY, "%d tokens exceed max_pos %d", n_tokens, kv->ctx->cfg.max_pos);
+    {
+        const rs_status s = import_check(kv, layer, n_tokens);
+        if (s != RS_OK) return s;
+    }
     if (n_tokens == 0) {
         kv->len[layer] = 0;
+        if (kv->paged()) kv->give_back_pages(layer, 0);
         return RS_OK;
     }
     if (!k_codes || !v_codes) return fail(RS_EINVAL, "k_codes / v_codes is null");
     if (!kv->ctx->has_device) return fail(RS_EHIP, "no HIP device");
+    if (kv->paged()) {
+        kv->take_pages(layer, n_tokens);
+        kv->give_back_pages(layer, n_tokens);
+    }
     const rs_status s = fp8_import(kv, layer, nullptr, nullptr, (const uint8_t*)k_codes, (const uint8_t*)v_codes, n_tokens,
                                    reinterpret_cast<hipStream_t>(stream));
     if (s == RS_OK) kv->len[layer] = n_tokens;

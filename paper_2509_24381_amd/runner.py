@@ -65,9 +65,10 @@ class LayerStack:
     def new_cache_fp8(self, capacity: int, k_scale: float = 1.0, v_scale: float = 1.0) -> KVCache:
         return self.ctx.kv_alloc_fp8(self.n_layers, capacity, k_scale, v_scale)
 
-    def new_pool(self, n_pages: int) -> KVPool:
-        """A pool of KV pages (64 tokens of one layer each); `pool.new_cache(stack.n_layers)` gives growable caches."""
-        return KVPool(self.ctx, n_pages)
+    def new_pool(self, n_pages: int, fp8: bool = False) -> KVPool:
+        """A pool of KV pages (64 tokens of one layer each; fp8: of E4M3 bytes); `pool.new_cache(stack.n_layers)` gives
+        growable caches."""
+        return KVPool(self.ctx, n_pages, fp8=fp8)
 
     def prefill_prompt(self, x_dev, chunks: Sequence[Tuple[int, int]], kv: KVCache, keep_layer_outputs: bool = False):
         """Runs one request's prompt chunk by chunk through all layers.

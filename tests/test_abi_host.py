@@ -327,3 +327,33 @@ def test_8bit_cache_argument_checks_on_the_host(lib):
     assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8], [70], X(70), X(70), Mem(ws1 + per_token * 128 - 1))) == "RS_EWORKSPACE"
     assert status_of(lambda: ctx.prefill_batch(w, 0, [kv8], [70], X(70), X(70), Mem(ws1 + per_token * 128))) == "RS_EHIP"
     assert kv8.length(0) == 0
+
+
+def test_8bit_page_pools_on_the_host(lib):
+    """An 8-bit pool has half-size pages and serves 8-bit caches only; a bfloat16 pool serves bfloat16 caches only."""
+    ctx = Context(tiny_cfg())
+    assert lib.rs_kv_page_bytes_fp8(ctx.handle) == lib.rs_kv_page_bytes(ctx.handle) // 2 == 2 * 2 * 64 * 64
+    h = C.c_void_p()
+    page = lib.rs_kv_page_bytes_fp8(ctx.handle)
+    assert lib.rs_kv_pool_create_fp8(ctx.handle, 0x6D0000000000, page - 1, C.byref(h)) == -3
+    assert lib.rs_kv_pool_create_fp8(ctx.handle, 0x6D0000000000, 7 * page + 5, C.byref(h)) == 0, lib.rs_last_error()
+    pool8 = C.c_void_p(h.value)
+    assert lib.rs_kv_pool_pages(pool8) == 7 and lib.rs_kv_pool_is_fp8(pool8) == 1 and lib.rs_kv_pool_is_fp8(None) == -1
+    pool16 = make_pool(lib, ctx, 3)
+    assert lib.rs_kv_pool_is_fp8(pool16) == 0
+    assert lib.rs_kv_alloc_paged(ctx.handle, pool8, 2, C.byref(h)) == -4                       # kinds do not mix
+    assert lib.rs_kv_alloc_paged_fp8(ctx.handle, pool16, 2, 1.0, 1.0, C.byref(h)) == -4
+    assert lib.rs_kv_alloc_paged_fp8(ctx.handle, pool8, 2, 0.0, 1.0, C.byref(h)) == -1          # scales as for rs_kv_alloc_fp8
+    assert lib.rs_kv_alloc_paged_fp8(ctx.handle, pool8, 0, 1.0, 1.0, C.byref(h)) == -1
+    assert lib.rs_kv_alloc_paged_fp8(ctx.handle, pool8, 2, 0.5, 2.0, C.byref(h)) == 0, lib.rs_last_error()
+    kv = binding.KVCache(ctx, h.value, None)
+    assert kv.is_fp8 and kv.capacity == 0 and lib.rs_kv_pool_free_pages(pool8) == 7
+    # imports count pages like prefill calls do: 8 pages for 500 tokens, the pool has 7
+    assert lib.rs_kv_import_codes(kv.handle, 0, 0x7B0000000000, 0x7B0000100000, 500, None) == -2
+    assert lib.rs_kv_import(kv.handle, 0, 0x7B0000000000, 0x7B0000100000, 500, None) == -2
+    assert lib.rs_kv_pool_free_pages(pool8) == 7
+    assert lib.rs_kv_import_codes(kv.handle, 0, 0x7B0000000000, 0x7B0000100000, 513, None) == -2     # beyond max_pos = 512
+    assert lib.rs_kv_pool_destroy(pool8) == -4
+    lib.rs_kv_free(kv.handle)
+    kv.handle = None
+    assert lib.rs_kv_pool_destroy(pool8) == 0 and lib.rs_kv_pool_destroy(pool16) == 0

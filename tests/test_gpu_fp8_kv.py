@@ -239,3 +239,94 @@ def test_error_paths_of_8bit_caches():
         kv16.export_codes(0)
     assert e.value.status_name == "RS_ESTATE"
     torch.cuda.synchronize()
+
+
+def test_paged_8bit_caches_match_contiguous_ones_bit_for_bit():
+    """Three requests of a two-layer stack advance in interleaved rounds on one pool of 8-bit pages, so their pages end up
+    scattered; every round's output and every final cache (codes and values) must equal what contiguous 8-bit caches
+    give.  Then pages go back to the pool as documented."""
+    r = R()
+    shape = synth.LayerShape("small128", 256, 4, 2, 128, 512)
+    ws = [synth.layer_weights(shape, 91 + l, gains="uniform") for l in range(2)]
+    lens_total = (300, 517, 130)
+    stack = r.LayerStack(shape, ws, max_tokens=512, max_requests=3, max_pos=1024, fp8_visible_tokens=sum(lens_total) + 3 * 64)
+    prompts = [synth.prompt_rows([("image", n // 2), ("text", n - n // 2)], shape.hidden, 95 + i) for i, n in enumerate(lens_total)]
+    rounds = [[70, 0, 64], [1, 200, 0], [129, 63, 66], [100, 254, 0]]
+    pages_for = lambda t: (t + 63) // 64
+
+    def run(paged):
+        pool = stack.new_pool(2 * sum(pages_for(n) for n in lens_total), fp8=True) if paged else None
+        kvs = [pool.new_cache(2, 0.5, 0.25) if paged else stack.new_cache_fp8(n, 0.5, 0.25) for n in lens_total]
+        assert all(kv.is_fp8 for kv in kvs)
+        done = [0, 0, 0]
+        outs = []
+        for lens in rounds:
+            x = r.to_device_bf16(np.concatenate([p[d:d + n] for p, d, n in zip(prompts, done, lens)], axis=0))
+            y = torch.empty_like(x)
+            stack.ctx.prefill_model_batch(stack.layers, kvs, lens, x, y, stack.ws)
+            outs.append(r.to_numpy_f32(y))
+            done = [d + n for d, n in zip(done, lens)]
+            if paged:
+                assert pool.free_pages == pool.pages - 2 * sum(pages_for(d) for d in done)
+        codes = [[tuple(t.cpu().numpy() for t in kv.export_codes(l)) for l in range(2)] for kv in kvs]
+        values = [[tuple(r.to_numpy_f32(t) for t in kv.export(l)) for l in range(2)] for kv in kvs]
+        return outs, codes, values, pool, kvs
+
+    outs_c, codes_c, values_c, _, _ = run(False)
+    outs_p, codes_p, values_p, pool, kvs = run(True)
+    for a, b in zip(outs_c, outs_p):
+        np.testing.assert_array_equal(a, b)
+    for ca, cb, va, vb in zip(codes_c, codes_p, values_c, values_p):
+        for l in range(2):
+            for j in range(2):
+                np.testing.assert_array_equal(ca[l][j], cb[l][j])
+                assert same_bits(va[l][j], vb[l][j])
+    assert pool.page_bytes == 2 * shape.n_kv_heads * 64 * shape.head_dim
+    free0 = pool.free_pages
+    kvs[1].truncate(0, 130)
+    assert pool.free_pages == free0 + pages_for(517) - pages_for(130)
+    kvs[1].reset()
+    assert pool.free_pages == free0 + 2 * pages_for(517)
+
+
+def test_paged_8bit_export_import_across_argument_windows_and_pool_limits():
+    """16500 tokens need two windows of page numbers in the export / import kernels.  Codes imported into a paged cache come
+    back unchanged; values imported through the store formula give the oracle's codes; a chunk on top of them matches a
+    contiguous 8-bit cache; the pool refuses what it cannot hold before anything runs."""
+    r = R()
+    from paper_2509_24381_amd.binding import RsError
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 101)
+    n, t = 16500, 60
+    stack = r.LayerStack(shape, [w], max_tokens=64, max_requests=1, max_pos=n + 64, fp8_visible_tokens=n + t + 64)
+    rng = np.random.default_rng(102)
+    pool = stack.new_pool((n + t + 63) // 64 + 1, fp8=True)
+    kv = pool.new_cache(1, 0.25, 0.5)
+    ck = rng.integers(0, 0x7F, (n, shape.n_kv_heads, shape.head_dim), dtype=np.uint8)
+    cv = rng.integers(0x80, 0xFF, (n, shape.n_kv_heads, shape.head_dim), dtype=np.uint8)
+    kv.import_codes(0, torch.from_numpy(ck).cuda(), torch.from_numpy(cv).cuda())
+    assert kv.length(0) == n and pool.free_pages == pool.pages - (n + 63) // 64
+    bk, bv = (c.cpu().numpy() for c in kv.export_codes(0))
+    np.testing.assert_array_equal(bk, ck)
+    np.testing.assert_array_equal(bv, cv)
+    k = synth.bf16_round(rng.normal(0, 1, ck.shape).astype(np.float32))
+    v = synth.bf16_round(rng.normal(0, 1, ck.shape).astype(np.float32))
+    kv.import_(0, r.to_device_bf16(k), r.to_device_bf16(v))
+    bk, bv = (c.cpu().numpy() for c in kv.export_codes(0))
+    np.testing.assert_array_equal(bk, kv_store(k, 0.25))
+    np.testing.assert_array_equal(bv, kv_store(v, 0.5))
+    flat = stack.new_cache_fp8(n + t, 0.25, 0.5)
+    flat.import_codes(0, torch.from_numpy(bk).cuda(), torch.from_numpy(bv).cuda())
+    x = r.to_device_bf16(synth.prompt_rows([("text", t)], shape.hidden, 103))
+    y_paged = r.to_numpy_f32(stack.prefill_batch(0, [kv], [t], x))
+    y_flat = r.to_numpy_f32(stack.prefill_batch(0, [flat], [t], x))
+    np.testing.assert_array_equal(y_paged, y_flat)
+    assert pool.free_pages == pool.pages - (n + t + 63) // 64
+    # the pool has one page left: a second cache may take 64 tokens, not 65 (asked for in two calls of a 64-row budget)
+    other = pool.new_cache(1)
+    assert pool.free_pages == 1
+    stack.prefill_batch(0, [other], [64], torch.cat([x, x[:4]], dim=0))
+    with pytest.raises(RsError) as e:
+        stack.prefill_batch(0, [other], [1], x[:1])
+    assert e.value.status_name == "RS_ECAPACITY" and other.length(0) == 64 and pool.free_pages == 0
+    torch.cuda.synchronize()
