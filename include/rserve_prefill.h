@@ -13,7 +13,8 @@
  *     -> append k~,v to the request's KV cache -> causal GQA attention of the chunk against the
  *     whole cache -> r = x + o Wo^T -> y = r + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T,  h2 = rmsnorm(r)
  *
- * with bf16 storage (inputs, weights, KV cache, outputs) and fp32 accumulation.  The paper does
+ * with bf16 storage (inputs, weights, KV cache - optionally 8-bit, see rs_kv_alloc_fp8 -, outputs) and fp32
+ * accumulation.  The paper does
  * not spell out the layer; it is the pre-norm decoder block of the model family the paper serves
  * (section 4.1.1), with sequential 1-D rotary positions.
  *
@@ -47,7 +48,7 @@ typedef enum rs_status {
     RS_EINVAL = -1,     /* null / misaligned pointer, negative size, bad layer index, duplicate request, shape the kernels do not support */
     RS_ECAPACITY = -2,  /* chunk does not fit the KV cache capacity or the RoPE table (max_pos) */
     RS_EWORKSPACE = -3, /* workspace smaller than rs_workspace_bytes() for this call */
-    RS_ESTATE = -4,     /* handle used with a context it was not created for */
+    RS_ESTATE = -4,     /* handle used with a context, pool or kind of cache it does not belong to; pool destroyed while in use */
     RS_EHIP = -5        /* a HIP runtime call failed; see rs_last_error() */
 } rs_status;
 
