@@ -399,6 +399,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                                                  __builtin_amdgcn_readfirstlane(d_wsoff + d_koff), 0, 0);
     };
 
+    const bool wave_has_rows = m0 + wave * 64 < a.M;   // (uniform per wavefront)
+
     // ---- weight fragment addresses inside a slot: row l32 of unit i at i*4096 + l32*128, chunk (2 kk + half) swizzled
     uint32_t aw[4];
 #pragma unroll
@@ -500,6 +502,23 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
         // tile start: xbuf[0 .. XD - 1] hold (or are receiving) the tile's first token fragments; its first weight step was
         // published by the previous tile's last barrier (by the prologue for the first tile)
         asm volatile("s_barrier" ::: "memory");
+        // A wavefront whose 64 rows all lie past M (a call of few rows, or the ragged end of the last block) only does its
+        // share of the weight DMA and meets the others at their barriers: every token load, even one that falls outside
+        // the buffer, takes its 16 clocks of the compute unit's one vector-memory pipe (32 KB of token fragments per step
+        // and workgroup, whatever the tile's width), and with one or two units per tile that pipe, not the matrix pipe, is
+        // what a step waits for.  Its queue then holds weight loads only: the next step's have landed when at most those
+        // of the AHEAD - 2 steps behind it are in flight.
+        if (!wave_has_rows) {
+            for (int s = 0; s < ns; ++s) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * NT) : "memory");
+                asm volatile("s_barrier" ::: "memory");
+                static_for<0, NT>([&](auto kc) { load_w(kc); });
+                if (__builtin_expect(d_nt > NT, 0)) load_w(std::integral_constant<int, NT < MAXNT ? NT : 0>{});
+                stream_advance();
+                c_slot = (c_slot + SLOT_BYTES) & (RING_BYTES - 1);
+            }
+            return;
+        }
         static_for<0, NT>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
         // step number s multiplies buffer s mod XB and loads the fragments of step s + XD into the buffer step s - 1 used
         int s = 0;
