@@ -123,7 +123,7 @@ RS_DEVICE u32x4 pair_runs(bf16x4 even_run, bf16x4 odd_run) {
 // unit unit0 + i.  Per-row inputs and all outputs go through buffer resources sized to M rows, so lanes whose token lies
 // past M read zeros and store nothing without any divergent branch (a divergent branch here, inside the tile loop, makes
 // the compiler keep the whole pipeline's scalar state in vector registers).
-template <int EPI, int NT>
+template <int EPI, int NT, int USTRIDE = 1>
 RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base, int unit0, int half, int l32, int split) {
     constexpr int RSRC_FLAGS = 0x00020000;
     const int m_pad = (a.M + 31) & ~31;  // fragment-major buffers hold whole blocks of 32 tokens
@@ -146,7 +146,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     for (int e = 0; e < 4; ++e)
                         o[q][e] = f32_to_bf16(silu_f32(acc[i][j][4 * q + e] * sc) * (acc[i][j][8 + 4 * q + e] * sc));
                 // lower lanes: features 16u..16u+7 (first half of the k-step), upper lanes: 16u+8..16u+15 (second half)
-                __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[0], o[1]), r_out, oblk + (uint32_t)(unit0 + i) * 1024u, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[0], o[1]), r_out, oblk + (uint32_t)(unit0 + i * USTRIDE) * 1024u, 0, 0);
             }
         } else if constexpr (EPI == EPI_QKV_ROPE) {
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, a.M * a.ldo * 2, RSRC_FLAGS);
@@ -161,7 +161,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             const uint32_t orow = (uint32_t)m * (uint32_t)a.ldo * 2u;
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
-                const int gu = unit0 + i;
+                const int gu = unit0 + i * USTRIDE;
                 if (gu * 32 < a.rope_cols) {
                     // rows 0..15 of the unit are features f..f+15 of the head's first half, rows 16..31 their partners
                     const int uh = gu & ((1 << uph_shift) - 1);
@@ -228,7 +228,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             for (int i = 0; i < NT; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = (unit0 + i) * 32 + 8 * q + 4 * half;
+                    const int n = (unit0 + i * USTRIDE) * 32 + 8 * q + 4 * half;
                     f32x4 o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), r_out, orow + (uint32_t)n * 4u, 0, 0);
                 }
@@ -246,7 +246,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                 bf16x4 o[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const uint32_t n = (uint32_t)((unit0 + i) * 32 + 8 * q + 4 * half);
+                    const uint32_t n = (uint32_t)((unit0 + i * USTRIDE) * 32 + 8 * q + 4 * half);
                     const uint32_t roff = a.resid_frag ? frag_offset_bytes(m, n, a.ldr) : ((uint32_t)m * (uint32_t)a.ldr + n) * 2u;
                     const bf16x4 r4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_raw_buffer_load_b64(r_res, roff, 0, 0));
 #pragma unroll
@@ -258,14 +258,14 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                 }
 #pragma unroll
                 for (int pr = 0; pr < 2; ++pr) {  // lower lanes store the even 8-feature group of the pair, upper lanes the odd one
-                    const uint32_t n = (uint32_t)((unit0 + i) * 32 + 16 * pr + 8 * half);
+                    const uint32_t n = (uint32_t)((unit0 + i * USTRIDE) * 32 + 16 * pr + 8 * half);
                     const uint32_t ooff = a.out_frag ? frag_offset_bytes(m, n, a.ldo) : ((uint32_t)m * (uint32_t)a.ldo + n) * 2u;
                     __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[2 * pr], o[2 * pr + 1]), r_out, ooff, 0, 0);
                 }
                 // the two half-waves hold the two halves of this token's 32 features of the unit; half 0 stores the sum
                 // (an empty resource when no sums are wanted; half 1 and rows past M aim outside it)
                 ss += __shfl_xor(ss, 32, WAVE);
-                const uint32_t soff = half ? 0x80000000u : ((uint32_t)m * (uint32_t)(a.N >> 5) + (uint32_t)(unit0 + i)) * 4u;
+                const uint32_t soff = half ? 0x80000000u : ((uint32_t)m * (uint32_t)(a.N >> 5) + (uint32_t)(unit0 + i * USTRIDE)) * 4u;
                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss), r_ss, soff, 0, 0);
             }
         }
@@ -283,8 +283,18 @@ RS_DEVICE void tie_wait_lgkm0(bf16x8 (&w)[NT]) {
 #pragma unroll
     for (int i = 1; i < NT; ++i) asm volatile("" : "+v"(w[i]));
 }
-template <int EPI, int MAXNT = GS_MAX_NT, int SLOTS = GS_SLOTS, int OCC = 1, int XD = 1>
+// WT of the 4 wavefronts are stacked along the tokens (64 rows each: a workgroup owns a block of 64 WT rows); the other
+// WU = 4 / WT ways they split the units of a tile between them (wavefront (tw, uw) multiplies units uw, uw + WU, ...), and
+// strips and tiles are made of groups of WU units.  WT = 2 serves the narrow launches of short calls: a step then moves
+// 16 KB of token fragments and 8 KB of weights through the vector-memory pipe for two units, where 256 rows x one unit
+// move 32 + 4 KB for one.
+template <int EPI, int MAXNT = GS_MAX_NT, int SLOTS = GS_SLOTS, int OCC = 1, int XD = 1, int WT = 4>
 __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
+    constexpr int WU = 4 / WT;
+    constexpr int BM = 64 * WT;
+    static_assert(WT == 2 || WT == 4, "wavefronts along the tokens");
+    static_assert(MAXNT % WU == 0, "a tile is a whole number of unit groups");
+    static_assert(WT == 4 || MAXNT == 2, "wavefronts split units in the narrow geometry only");
     constexpr int XB = XD + 1;   // token-fragment buffers: the step being multiplied and the XD steps in flight behind it
     constexpr int SLOT_BYTES = MAXNT * 32 * GS_BK * 2;   // up to 32 MAXNT weight rows of one step
     constexpr int RING_BYTES = SLOTS * SLOT_BYTES;       // a power of two
@@ -296,6 +306,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tw = wave & (WT - 1), uw = wave / WT;   // place along the tokens and among the unit-splitting wavefronts
     const int half = lane >> 5;
     const int l32 = lane & 31;
 
@@ -313,16 +324,18 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     const int logical = (xcd < wrem ? xcd * (wbase + 1) : wrem * (wbase + 1) + (xcd - wrem) * wbase) + loc;
     const int tm = logical % a.tiles_m;
     const int strip = logical / a.tiles_m;
-    const int m0 = tm * GS_BM;
+    const int m0 = tm * BM;
 
     // ---- the strip's units and its tiles (sizes differ by at most one, smaller ones first: the load stream then never
     //      issues fewer loads per step than the waits of the tile being multiplied assume)
-    const int nu = a.N >> 5;
+    //      (counted in groups of WU units from here to the tile loop)
+    const int nu = (a.N >> 5) / WU;
     const int ub = nu / a.strips, ur = nu % a.strips;
     const int u_first = strip * ub + min(strip, ur);
     const int u_count = ub + (strip < ur ? 1 : 0);
-    if (u_count == 0) return;  // more strips than units: never launched this way, and uniform for the whole workgroup
-    const int ntiles = (u_count + MAXNT - 1) / MAXNT;
+    if (u_count == 0) return;  // more strips than groups: never launched this way, and uniform for the whole workgroup
+    constexpr int MAXG = MAXNT / WU;
+    const int ntiles = (u_count + MAXG - 1) / MAXG;
     const int tb = u_count / ntiles;
     const int n_small = ntiles - u_count % ntiles;  // tiles [0, n_small) have tb units, the rest tb + 1
 
@@ -342,7 +355,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     const uint32_t x_block_bytes = (uint32_t)(a.K >> 4) * 1024u;  // one block of 32 tokens, all of K
     const __amdgpu_buffer_rsrc_t rx =
         __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, ((a.M + 31) >> 5) * (int)x_block_bytes, 0x00020000);
-    const uint32_t xv0 = (uint32_t)((m0 >> 5) + wave * 2) * x_block_bytes + (uint32_t)half * 512u + (uint32_t)l32 * 16u;
+    const uint32_t xv0 = (uint32_t)((m0 >> 5) + tw * 2) * x_block_bytes + (uint32_t)half * 512u + (uint32_t)l32 * 16u;
     const uint32_t xv1 = xv0 + x_block_bytes;
     uint32_t x_koff = xk0;  // byte offset of the next step to load inside a token block
     int x_s = 0;
@@ -377,8 +390,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     // one store through a selected address, which keeps that state in scratch memory)
     auto stream_enter_tile = [&]() {
         const bool in_strip = d_tile < ntiles;  // past the strip's last tile the remaining loads of the pipeline move nothing
-        const int unit0 = u_first + d_tile * tb + max(d_tile - n_small, 0);
-        d_nt = tb + (d_tile >= n_small ? 1 : 0);
+        const int unit0 = (u_first + d_tile * tb + max(d_tile - n_small, 0)) * WU;
+        d_nt = (tb + (d_tile >= n_small ? 1 : 0)) * WU;
         d_wsoff = in_strip ? (uint32_t)unit0 * 32u * (uint32_t)a.K * 2u : 0u;
         d_vw = in_strip ? vw0 : DEAD;
     };
@@ -399,13 +412,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                                                  __builtin_amdgcn_readfirstlane(d_wsoff + d_koff), 0, 0);
     };
 
-    const bool wave_has_rows = m0 + wave * 64 < a.M;   // (uniform per wavefront)
+    const bool wave_has_rows = m0 + tw * 64 < a.M;   // (uniform per wavefront)
 
     // ---- weight fragment addresses inside a slot: row l32 of unit i at i*4096 + l32*128, chunk (2 kk + half) swizzled
     uint32_t aw[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        aw[kk] = lds0 + (uint32_t)l32 * 128u + (((uint32_t)(kk * 2 + half) ^ (uint32_t)((l32 >> 1) & 7)) * 16u);
+        aw[kk] = lds0 + (uint32_t)uw * 4096u + (uint32_t)l32 * 128u + (((uint32_t)(kk * 2 + half) ^ (uint32_t)((l32 >> 1) & 7)) * 16u);
     uint32_t c_slot = 0;  // ring slot of the step being multiplied
 
     // ---- fill the pipeline: W(0) .. W(AHEAD - 2), X(0) .. X(XD - 1), W(AHEAD - 1)
@@ -425,28 +438,29 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     auto run_tile = [&](auto ntc, const int unit0) {
-        constexpr int NT = decltype(ntc)::value;
-        constexpr int SL = 2 * NT;   // MFMAs (= slots for memory instructions) per k-step
-        f32x16 acc[NT][2];
+        constexpr int NT = decltype(ntc)::value;   // units of the tile (= weight DMA instructions per step and wavefront)
+        constexpr int NTW = NT / WU;               // units this wavefront multiplies
+        constexpr int SL = 2 * NTW;  // MFMAs (= slots for memory instructions) per k-step
+        f32x16 acc[NTW][2];
 #pragma unroll
-        for (int i = 0; i < NT; ++i)
+        for (int i = 0; i < NTW; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        bf16x8 wa[NT], wb[NT];
+        bf16x8 wa[NTW], wb[NTW];
 
-        auto read_w = [&](auto ic, bf16x8 (&wf)[NT], const uint32_t addr) {
+        auto read_w = [&](auto ic, bf16x8 (&wf)[NTW], const uint32_t addr) {
             constexpr int i = decltype(ic)::value;
-            RS_DS_READ_B128(wf[i], addr, i * 4096);
+            RS_DS_READ_B128(wf[i], addr, i * WU * 4096);
         };
         // one k-step of 2 NT MFMAs on (wf, xc[.][KK]); memory instruction number o of the phase rides behind MFMA number
         // o (or several per MFMA when there are more instructions than MFMAs): first the NT fragment reads of the next
         // k-step, then the phase's EXTRA loads
-        auto phase = [&](auto kkc, bf16x8 (&wf)[NT], bf16x8 (&xc)[2][4], bf16x8 (&wnext)[NT], const uint32_t wnext_addr,
+        auto phase = [&](auto kkc, bf16x8 (&wf)[NTW], bf16x8 (&xc)[2][4], bf16x8 (&wnext)[NTW], const uint32_t wnext_addr,
                          auto extra_count, auto&& extra) {
             constexpr int KK = decltype(kkc)::value;
-            constexpr int LA = NT + decltype(extra_count)::value;
+            constexpr int LA = NTW + decltype(extra_count)::value;
             static_for<0, SL>([&](auto qc) {
                 constexpr int q = decltype(qc)::value;
                 constexpr int i = q >> 1, j = q & 1;
@@ -455,8 +469,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                 constexpr int o_hi = (LA <= SL) ? (q + 1 < LA ? q + 1 : LA) : ((q + 1) * LA / SL);
                 static_for<o_lo, o_hi>([&](auto oc) {
                     constexpr int o = decltype(oc)::value;
-                    if constexpr (o < NT) read_w(oc, wnext, wnext_addr);
-                    else extra(std::integral_constant<int, o - NT>{});
+                    if constexpr (o < NTW) read_w(oc, wnext, wnext_addr);
+                    else extra(std::integral_constant<int, o - NTW>{});
                 });
                 RS_FENCE();
             });
@@ -466,14 +480,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
         // together with the DMA of the weights three steps ahead
         auto step = [&](bf16x8 (&xc)[2][4], bf16x8 (&xn)[2][4]) {
             const uint32_t n_slot = (c_slot + SLOT_BYTES) & (RING_BYTES - 1);
-            tie_wait_lgkm0<NT>(wa);
+            tie_wait_lgkm0<NTW>(wa);
             phase(std::integral_constant<int, 0>{}, wa, xc, wb, aw[1] + c_slot, std::integral_constant<int, 4>{},
                   [&](auto ec) { load_x(ec, xn); });
-            tie_wait_lgkm0<NT>(wb);
+            tie_wait_lgkm0<NTW>(wb);
             phase(std::integral_constant<int, 1>{}, wb, xc, wa, aw[2] + c_slot, std::integral_constant<int, 4>{},
                   [&](auto ec) { load_x(std::integral_constant<int, decltype(ec)::value + 4>{}, xn); });
             x_advance();
-            tie_wait_lgkm0<NT>(wa);  // also: every LDS read of k-steps 0..2 has landed
+            tie_wait_lgkm0<NTW>(wa);  // also: every LDS read of k-steps 0..2 has landed
             // this wavefront's share of the next W step has landed when at most this step's 8 token loads and the loads of
             // the AHEAD - 2 steps before it (NT weight, 8 token) are still in flight
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 + (AHEAD - 2) * (NT + 8)) : "memory");
@@ -482,7 +496,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
             constexpr int W_A = (NT + 1) / 2, W_B = NT - W_A;
             phase(std::integral_constant<int, 2>{}, wa, xc, wb, aw[3] + c_slot, std::integral_constant<int, W_A>{},
                   [&](auto ec) { load_w(ec); });
-            tie_wait_lgkm0<NT>(wb);
+            tie_wait_lgkm0<NTW>(wb);
             // (the stream's bookkeeping - scalar work and a rarely taken branch - rides behind an MFMA in the middle of the
             // phase like a memory instruction: left after the phase's last MFMA it holds up the next step's first one by
             // about 150 clocks, with one wavefront per SIMD and nothing else to issue)
@@ -491,8 +505,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                       if constexpr (decltype(ec)::value < W_B) {
                           load_w(std::integral_constant<int, decltype(ec)::value + W_A>{});
                       } else {
-                          if (__builtin_expect(d_nt > NT, 0))
-                              load_w(std::integral_constant<int, NT < MAXNT ? NT : 0>{});  // the stream is in a wider tile
+                          if (__builtin_expect(d_nt > NT, 0))   // the stream is in a wider tile: one more group of units
+                              static_for<0, WU>([&](auto gc) {
+                                  constexpr int k = NT + decltype(gc)::value;
+                                  load_w(std::integral_constant<int, k < MAXNT ? k : 0>{});
+                              });
                           stream_advance();
                       }
                   });
@@ -513,13 +530,17 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * NT) : "memory");
                 asm volatile("s_barrier" ::: "memory");
                 static_for<0, NT>([&](auto kc) { load_w(kc); });
-                if (__builtin_expect(d_nt > NT, 0)) load_w(std::integral_constant<int, NT < MAXNT ? NT : 0>{});
+                if (__builtin_expect(d_nt > NT, 0))
+                    static_for<0, WU>([&](auto gc) {
+                        constexpr int k = NT + decltype(gc)::value;
+                        load_w(std::integral_constant<int, k < MAXNT ? k : 0>{});
+                    });
                 stream_advance();
                 c_slot = (c_slot + SLOT_BYTES) & (RING_BYTES - 1);
             }
             return;
         }
-        static_for<0, NT>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
+        static_for<0, NTW>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
         // step number s multiplies buffer s mod XB and loads the fragments of step s + XD into the buffer step s - 1 used
         int s = 0;
         for (; s + XB <= ns; s += XB)
@@ -550,14 +571,16 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                         for (int kk = 0; kk < 4; ++kk) xbuf[b][j][kk] = moved[b][j][kk];
             }
         });
-        tie_wait_lgkm0<NT>(wa);  // the look-ahead read behind the last step (discarded: the next tile reads its own)
-        gemm_epilogue<EPI, NT>(a, acc, m0 + wave * 64, unit0, half, l32, split);
+        tie_wait_lgkm0<NTW>(wa);  // the look-ahead read behind the last step (discarded: the next tile reads its own)
+        gemm_epilogue<EPI, NTW, WU>(a, acc, m0 + tw * 64, unit0 + uw, half, l32, split);
     };
 
     for (int t = 0; t < ntiles; ++t) {
-        const int nt = tb + (t >= n_small ? 1 : 0);
-        const int unit0 = u_first + t * tb + max(t - n_small, 0);
-        if constexpr (MAXNT == 2) {
+        const int nt = (tb + (t >= n_small ? 1 : 0)) * WU;
+        const int unit0 = (u_first + t * tb + max(t - n_small, 0)) * WU;
+        if constexpr (MAXNT == 2 && WU == 2) {
+            run_tile(std::integral_constant<int, 2>{}, unit0);   // one group of two units
+        } else if constexpr (MAXNT == 2) {
             if (nt == 1) run_tile(std::integral_constant<int, 1>{}, unit0);
             else run_tile(std::integral_constant<int, 2>{}, unit0);
         } else

@@ -81,6 +81,7 @@ struct rs_ctx {
     int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
     int attn_variant = 1;     // RS_ATTN environment variable: 2 the wide software-pipelined attention kernel (256 rows per
                               // workgroup), 1 the 128-row software-pipelined one, 0 the plain one
+    int gemm_pairs = 1;       // RS_PAIRS environment variable: 0 never lets two wavefronts of a GEMM workgroup split a pair of units
     int gemm_narrow = 1;      // RS_NARROW environment variable: 0 never uses the narrow GEMM geometry; otherwise launches of at most
     int narrow_max_tiles_m = 1;  // narrow_max_tiles_m (RS_NARROW_TM) token blocks whose strips would hold at most 2 units use it
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
@@ -271,6 +272,21 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     const int steps = a.K / GS_BK;
     a.steps_per_split = (steps + splits - 1) / splits;
     splits = (steps + a.steps_per_split - 1) / a.steps_per_split;  // no empty K range
+    // A call of 129 to 256 rows whose strips would hold one pair of units each: blocks of 128 rows, two wavefronts along
+    // the rows and two along the pair (16 KB of token fragments per step and workgroup instead of 32; measured: QKV 40 -> 35
+    // us at 256 rows; up to 128 rows, where half the wavefronts of a 256-row block idle anyway, it is slower).
+    if (c->gemm_narrow && c->gemm_pairs && a.M > GS_BM / 2 && a.M <= GS_BM && units % 2 == 0) {
+        const int tiles_m = (a.M + GS_BM / 2 - 1) / (GS_BM / 2);
+        const int strips = strips_for(c, tiles_m, splits, units / 2);
+        if (strips == units / 2) {
+            a.tiles_m = tiles_m;
+            a.strips = strips;
+            hipLaunchKernelGGL((gemm_strip_kernel<EPI, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>), dim3(tiles_m * strips, splits),
+                               dim3(256), GS_NARROW_LDS_BYTES, st, a);
+            RS_HIP(hipGetLastError());
+            return RS_OK;
+        }
+    }
     a.strips = strips_for(c, a.tiles_m, splits, units);
     dim3 grid(a.tiles_m * a.strips, splits);
     if (use_narrow(c, a.tiles_m, splits, units))
@@ -829,6 +845,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->mrope_b0 = c->mrope_b1 = f.head_dim / 2;  // 1-D RoPE: every pair turns with the first axis
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
     if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
+    if (const char* e = getenv("RS_PAIRS")) c->gemm_pairs = atoi(e);
     if (const char* e = getenv("RS_NARROW")) c->gemm_narrow = atoi(e);
     if (const char* e = getenv("RS_NARROW_TM")) c->narrow_max_tiles_m = atoi(e);
     if (const char* e = getenv("RS_ATTN_SPLIT")) c->attn_split = std::max(0, std::min(atoi(e), ATT_MAX_PARTS));
@@ -883,6 +900,10 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_QKV_ROPE, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)lm_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LM_ROWS * f.hidden * 4);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
