@@ -241,6 +241,41 @@ def test_export_import_round_trip_is_bit_exact():
         np.testing.assert_array_equal(r.to_numpy_f32(v2), v)
 
 
+@pytest.mark.parametrize("shape_name", ["small128", "wide_mlp"])
+def test_row_counts_around_every_wavefront_and_block_boundary(shape_name):
+    """The GEMMs choose their geometry and the work of their wavefronts by the row count of the call: wavefronts whose 64
+    rows lie past the end idle, calls of 129 to 256 rows on narrow strips run in blocks of 128 rows with the units of a
+    pair split between wavefronts, longer calls in blocks of 256.  One call per row count on a prior cache of 100 tokens,
+    each against the oracle, and each bit-identical to the same rows taken from a longer call (a row's result does not
+    depend on how many rows the call has)."""
+    r = R()
+    shape = (synth.LayerShape("small128", 256, 4, 2, 128, 512) if shape_name == "small128"
+             else synth.LayerShape("wide_mlp", 512, 8, 2, 64, 4096))
+    w = synth.layer_weights(shape, 77, qkv_bias=True, gains="uniform")
+    stack = r.LayerStack(shape, [w], max_tokens=512, max_requests=1, max_pos=1024, qkv_bias=True)
+    prior, longest = 100, 400
+    x = synth.prompt_rows([("text", prior), ("image", longest)], shape.hidden, 78)
+    params = LayerParams.from_arrays(shape, w)
+    base = ChunkedPrefill(params)
+    base.prefill_chunk(x[:prior])
+    kv = stack.new_cache(prior + longest)
+    stack.prefill_batch(0, [kv], [prior], r.to_device_bf16(x[:prior]))
+    xd = r.to_device_bf16(x[prior:])
+    y_long = r.to_numpy_f32(stack.prefill_batch(0, [kv], [longest], xd))
+    k_long, v_long = (r.to_numpy_f32(t) for t in kv.export(0))
+    st = ChunkedPrefill(params, prior_k=base.k, prior_v=base.v)
+    want_long = st.prefill_chunk(x[prior:])
+    check("400 rows", y_long, want_long)
+    for t in (1, 31, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300):
+        kv.truncate(0, prior)
+        y = r.to_numpy_f32(stack.prefill_batch(0, [kv], [t], xd[:t]))
+        check(f"{t} rows", y, want_long[:t])
+        k, v = (r.to_numpy_f32(c) for c in kv.export(0))
+        # K~ and V of a row come out of the QKV GEMM alone: the same bits whatever the call's row count
+        np.testing.assert_array_equal(k, k_long[:prior + t])
+        np.testing.assert_array_equal(v, v_long[:prior + t])
+
+
 @pytest.mark.parametrize("env", [{"RS_SPLITK": "1"}, {"RS_SPLITK": "2"}, {"RS_SPLITK": "3"},
                                  {"RS_NCU": "1"}, {"RS_NCU": "3"}, {"RS_NCU": "7", "RS_SPLITK": "2"},
                                  {"RS_ATTN": "0"}, {"RS_ATTN": "2"}, {"RS_ATTN_SPLIT": "1"}, {"RS_ATTN_SPLIT": "3"},
