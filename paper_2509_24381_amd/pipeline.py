@@ -39,19 +39,23 @@ class StubEncoder:
 
 @dataclass
 class PipelineResult:
-    ttft_ms: float            # request arrival -> last prompt token prefilled (the first output token can be sampled)
+    ttft_ms: float            # request arrival -> last prompt token prefilled; with a head: -> first output token on the host
     encode_ms: float          # arrival -> last encoder batch delivered
     n_rounds: int
     n_encode_batches: int
     round_tokens: List[int]
+    first_token: int = -1     # arg max of the first-token logits (only with a head)
 
 
 def run_intra_request_pipeline(stack: LayerStack, segments: Sequence[Tuple[bool, int]], rows_dev, *, min_tokens: int,
-                               token_budget: int, encoder: StubEncoder, request_id: int = 1) -> Tuple[PipelineResult, object, object]:
+                               token_budget: int, encoder: StubEncoder, request_id: int = 1,
+                               head=None) -> Tuple[PipelineResult, object, object]:
     """Serves ONE request: Algorithm 1 feeds the encoder on its own stream, Algorithm 2 (with a single request in the
     queue) prefills on the current stream whatever has become schedulable.  rows_dev holds the prompt's final embedding
     rows (text rows are valid from the start; a multimodal item's rows count as available only once the encoder batch
-    that contains it has finished).  Returns timings, the request's KV cache and the last layer's output."""
+    that contains it has finished).  head = (final_norm_gain [H], w_lm [vocab, H]) bf16 device tensors: the time to first
+    token then includes the final RMSNorm and vocabulary projection of the last prompt row (rs_lm_head) and the arg max.
+    Returns timings, the request's KV cache and the last layer's output."""
     import torch
     sched = Scheduler(token_budget)
     sched.add_request(request_id, segments)
@@ -102,8 +106,12 @@ def run_intra_request_pipeline(stack: LayerStack, segments: Sequence[Tuple[bool,
         n = run_scheduled_round(stack, entries, {request_id: emb}, {request_id: kv}, {request_id: out})
         rounds += 1
         round_tokens.append(n)
+    first_token = -1
+    if head is not None:
+        logits = stack.ctx.lm_head(head[0], head[1], out[n_total - 1: n_total])
+        first_token = int(torch.argmax(logits[0]).item())      # (the copy to the host waits for the stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     res = PipelineResult(ttft_ms=(t1 - t0) * 1e3, encode_ms=((t_encode or t1) - t0) * 1e3, n_rounds=rounds,
-                         n_encode_batches=len(batches), round_tokens=round_tokens)
+                         n_encode_batches=len(batches), round_tokens=round_tokens, first_token=first_token)
     return res, kv, out

@@ -28,6 +28,9 @@ def main():
                     help="decoder layers the prefill runs through (the 4 synthetic layers are reused cyclically: same "
                          "cost as distinct weights, 1/7 of the memory)")
     ap.add_argument("--budget", type=int, default=2048)
+    ap.add_argument("--vocab", type=int, default=152064,
+                    help="rows of the vocabulary matrix of the first-token head (final RMSNorm + projection of the last prompt row, "
+                         "then the arg max, all inside the measured time); 0 stops the clock when the prefill is complete")
     ap.add_argument("--repeats", type=int, default=5)
     ap.add_argument("--batch-sizes", type=int, nargs="*", default=[256, 512, 1024, 2048, 4096, 1 << 30])
     args = ap.parse_args()
@@ -46,24 +49,31 @@ def main():
     segments = [(kind == "image", n) for kind, n in wl.segments]
     rows = runner.to_device_bf16(wl.prompt())
     enc = pipeline.StubEncoder(args.encoder_gflop_per_token)
+    head = None
+    if args.vocab > 0:
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        head = (torch.ones(wl.shape.hidden, device="cuda", dtype=torch.bfloat16),
+                (torch.randn(args.vocab, wl.shape.hidden, device="cuda", generator=gen) * 0.02).to(torch.bfloat16))
     n_mm = sum(n for mm, n in segments if mm)
     for c in args.batch_sizes:
         times, enc_times, res = [], [], None
         for rep in range(args.repeats + 1):
             res, kv, out = pipeline.run_intra_request_pipeline(stack, segments, rows, min_tokens=c, token_budget=args.budget,
-                                                               encoder=enc)
+                                                               encoder=enc, head=head)
             if rep:                      # the first repetition warms up
                 times.append(res.ttft_ms)
                 enc_times.append(res.encode_ms)
             del kv, out
         times.sort()
-        print(json.dumps({"metric": "time to first token of one request (prefill complete), intra-request pipeline",
+        print(json.dumps({"metric": "time to first token of one request (" + ("first token on the host" if head else "prefill complete")
+                                    + "), intra-request pipeline",
                           "embedding_batch_size": "whole request" if c >= n_mm else c,
                           "ttft_ms_median": times[len(times) // 2], "ttft_ms_min": times[0],
                           "encode_done_ms_median": sorted(enc_times)[len(enc_times) // 2],
                           "encode_batches": res.n_encode_batches, "prefill_rounds": res.n_rounds,
                           "prompt_tokens": wl.n_tokens, "multimodal_tokens": n_mm, "layers": args.layers,
-                          "token_budget": args.budget, "encoder_gflop_per_token": args.encoder_gflop_per_token}), flush=True)
+                          "token_budget": args.budget, "encoder_gflop_per_token": args.encoder_gflop_per_token,
+                          "vocab": args.vocab, "first_token": res.first_token}), flush=True)
 
 
 if __name__ == "__main__":

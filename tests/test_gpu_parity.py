@@ -316,6 +316,17 @@ def test_intra_request_pipeline_matches_unchunked_oracle():
         check(f"pipeline C={c} K", _np(k), k_ref)
         check(f"pipeline C={c} V", _np(v), v_ref)
         print(f"[pipeline] C={c}: {res.n_encode_batches} encoder batches, {res.n_rounds} rounds, ttft {res.ttft_ms:.2f} ms", flush=True)
+    # with a first-token head the harness ends in the final norm, the vocabulary projection of the last prompt row and the
+    # arg max: the token it reports must be (one of) the oracle's best on the row the library produced - the decision is
+    # taken on the same input, and a near tie within the logits' tolerance may fall either way
+    rng = np.random.default_rng(402)
+    gain = synth.bf16_round(rng.uniform(0.5, 1.5, shape.hidden).astype(np.float32))
+    w_lm = synth.bf16_round(rng.normal(0, 0.05, (1000, shape.hidden)).astype(np.float32))
+    res, kv, out = pipeline.run_intra_request_pipeline(stack, segs, _dev(rows), min_tokens=100, token_budget=64, encoder=enc,
+                                                       head=(_dev(gain), _dev(w_lm)))
+    logits = oracle.first_token_logits(_np(out)[-1:], gain, w_lm, shape.rms_eps)[0]
+    assert 0 <= res.first_token < 1000
+    assert logits[res.first_token] >= logits.max() - 1e-2 * np.abs(logits).max()
 
 
 def test_model_batch_equals_layer_by_layer_calls_bit_for_bit():
