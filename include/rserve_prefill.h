@@ -232,6 +232,11 @@ rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_lay
                                  rs_kv* const* kvs, const int* chunk_lens, int R,
                                  const void* x_dev, void* y_dev,
                                  void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+/* rs_prefill_model_batch with the rotary positions of rs_prefill_batch_mrope (the same positions for every layer). */
+rs_status rs_prefill_model_batch_mrope(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers,
+                                       rs_kv* const* kvs, const int* chunk_lens, int R, const int* positions,
+                                       const void* x_dev, void* y_dev,
+                                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* First output token (what "time to first token", the paper's latency metric in section 4.1.4, waits for): final
  * RMSNorm and vocabulary projection of n_rows hidden-state rows (the last prompt row of each request whose prefill has

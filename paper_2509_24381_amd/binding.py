@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "rs_kv_alloc_paged",
     "rs_kv_fp8_bytes", "rs_kv_alloc_fp8", "rs_kv_is_fp8", "rs_kv_export_codes", "rs_kv_import_codes", "rs_workspace_bytes_fp8kv",
     "rs_kv_page_bytes_fp8", "rs_kv_pool_create_fp8", "rs_kv_pool_is_fp8", "rs_kv_alloc_paged_fp8",
-    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_ctx_set_mrope_sections",
+    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_prefill_model_batch_mrope", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
     "rs_profile_enable", "rs_profile_sample_every", "rs_profile_read",
@@ -121,6 +121,7 @@ def load_library():
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
+        "rs_prefill_model_batch_mrope": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, C.POINTER(i), vp, vp, vp, sz, vp]),
         "rs_ctx_set_mrope_sections": (i, [vp, i, i, i]),
         "rs_prefill_batch_mrope": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, C.POINTER(i), vp, vp, vp, sz, vp]),
         "rs_lm_head_workspace_bytes": (sz, [vp, i]),
@@ -427,6 +428,19 @@ class Context:
         arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
         _check(self.lib.rs_prefill_model_batch(self.handle, arr_w, len(layers), arr_kv, arr_len, r, _ptr(x), _ptr(y),
                                                _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+        return y
+
+    def prefill_model_batch_mrope(self, layers: Sequence[PackedWeights], kvs: Sequence[KVCache], chunk_lens: Sequence[int],
+                                  positions, x, y, workspace, stream=None):
+        """prefill_model_batch with explicit (temporal, height, width) rotary positions [sum chunk_lens, 3] (host)."""
+        r = len(kvs)
+        flat = [int(v) for row in positions for v in row]
+        arr_pos = (C.c_int * max(len(flat), 1))(*flat)
+        arr_w = (_Weights * max(len(layers), 1))(*[l.struct for l in layers])
+        arr_kv = (C.c_void_p * max(r, 1))(*[k.handle.value for k in kvs])
+        arr_len = (C.c_int * max(r, 1))(*[int(n) for n in chunk_lens])
+        _check(self.lib.rs_prefill_model_batch_mrope(self.handle, arr_w, len(layers), arr_kv, arr_len, r, arr_pos, _ptr(x), _ptr(y),
+                                                     _ptr(workspace), workspace.numel(), _stream_handle(stream)))
         return y
 
     def lm_head(self, final_norm_gain, w_lm, x_rows, stream=None):

@@ -1351,16 +1351,16 @@ rs_status rs_prefill_batch_mrope(rs_ctx* ctx, const rs_layer_weights* packed, in
     return prefill_impl(ctx, packed, layer, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, stream, positions);
 }
 
-rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs,
-                                 const int* chunk_lens, int R, const void* x, void* y, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
+static rs_status model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs, const int* chunk_lens,
+                             int R, const int* positions3, const void* x, void* y, void* workspace, size_t workspace_bytes,
+                             void* stream) {
     if (!packed_layers) return fail(RS_EINVAL, "packed_layers is null");
     if (n_layers <= 0) return fail(RS_EINVAL, "n_layers = %d must be positive", n_layers);
     int T = 0;
     PoolNeed need;
     for (int l = 0; l < n_layers; ++l) {  // all checks first: a failing call leaves every cache untouched
         const rs_status s = prefill_check(ctx, &packed_layers[l], l, kvs, chunk_lens, R, x, y, workspace, workspace_bytes, &T,
-                                          nullptr, &need);
+                                          positions3, &need);
         if (s != RS_OK) return s;
     }
     {
@@ -1370,10 +1370,24 @@ rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_lay
     if (T > 0 && !ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
     if (T == 0) return RS_OK;
     for (int l = 0; l < n_layers; ++l) {  // layer 0 reads x; later layers work on y in place
-        const rs_status s = prefill_enqueue(ctx, &packed_layers[l], l, kvs, chunk_lens, R, T, l == 0 ? x : y, y, workspace, stream);
+        const rs_status s = prefill_enqueue(ctx, &packed_layers[l], l, kvs, chunk_lens, R, T, l == 0 ? x : y, y, workspace, stream,
+                                            positions3);
         if (s != RS_OK) return s;
     }
     return RS_OK;
+}
+
+rs_status rs_prefill_model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs,
+                                 const int* chunk_lens, int R, const void* x, void* y, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    return model_batch(ctx, packed_layers, n_layers, kvs, chunk_lens, R, nullptr, x, y, workspace, workspace_bytes, stream);
+}
+
+rs_status rs_prefill_model_batch_mrope(rs_ctx* ctx, const rs_layer_weights* packed_layers, int n_layers, rs_kv* const* kvs,
+                                       const int* chunk_lens, int R, const int* positions, const void* x, void* y, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+    if (!positions) return fail(RS_EINVAL, "positions is null");
+    return model_batch(ctx, packed_layers, n_layers, kvs, chunk_lens, R, positions, x, y, workspace, workspace_bytes, stream);
 }
 
 size_t rs_lm_head_workspace_bytes(const rs_ctx* c, int n_rows) {

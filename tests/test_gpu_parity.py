@@ -430,6 +430,44 @@ def test_three_axis_rotary_positions(shape_name, sections):
         stack.ctx.set_mrope_sections(sections[0] + 1, sections[1] - 1, sections[2])
 
 
+def test_all_layers_with_three_axis_positions_equal_the_layer_by_layer_calls():
+    """rs_prefill_model_batch_mrope is rs_prefill_batch_mrope layer after layer with the same positions: identical bits
+    in the output and in every cache, for two requests in one micro-batch, over two rounds."""
+    R = _runner()
+    shape = synth.TINY
+    sections = (8, 12, 12)
+    ws = [synth.layer_weights(shape, 720 + l, gains="uniform") for l in range(3)]
+    stack = R.LayerStack(shape, ws, max_tokens=128, max_requests=2, max_pos=256)
+    stack.ctx.set_mrope_sections(*sections)
+    rng = np.random.default_rng(721)
+    rows = [synth.prompt_rows([("image", 60), ("text", 30)], shape.hidden, 722), synth.prompt_rows([("text", 50)], shape.hidden, 723)]
+    pos = [np.stack([np.sort(rng.integers(0, 200, r.shape[0])) for _ in range(3)], axis=1) for r in rows]
+    rounds = [[(0, 40), (0, 50)], [(40, 90), (50, 50)]]
+    kv_a = [stack.new_cache(128) for _ in rows]
+    kv_b = [stack.new_cache(128) for _ in rows]
+    for rnd in rounds:
+        lens = [b - a for a, b in rnd]
+        x = _dev(np.concatenate([r[a:b] for r, (a, b) in zip(rows, rnd)]))
+        p = np.concatenate([q[a:b] for q, (a, b) in zip(pos, rnd)])
+        y_a = torch.empty_like(x)
+        stack.ctx.prefill_model_batch_mrope(stack.layers, kv_a, lens, p, x, y_a, stack.ws)
+        cur = x
+        for l in range(3):
+            nxt = torch.empty_like(x)
+            stack.ctx.prefill_batch_mrope(stack.layers[l], l, kv_b, lens, p, cur, nxt, stack.ws)
+            cur = nxt
+        torch.cuda.synchronize()
+        assert torch.equal(y_a, cur)
+    for ka, kb in zip(kv_a, kv_b):
+        for l in range(3):
+            for ta, tb in zip(ka.export(l), kb.export(l)):
+                assert torch.equal(ta, tb)
+    from paper_2509_24381_amd.binding import RsError
+    with pytest.raises(RsError) as e:     # a position beyond the table: refused before any layer runs
+        stack.ctx.prefill_model_batch_mrope(stack.layers, kv_a, [1, 0], [(0, 256, 0)], x[:1], y_a[:1], stack.ws)
+    assert e.value.status_name == "RS_ECAPACITY" and [kv.length(2) for kv in kv_a] == [90, 50]
+
+
 # ------------------------------------------------------------------ production shapes
 def test_workload2_7b_2048_budget512():
     wl = synth.workload(2)
