@@ -31,7 +31,7 @@
  *    streams).  The host side is not thread-safe: one thread at a time per rs_ctx.
  *  - rs_prefill_* calls are not for HIP graph capture: every call builds its descriptors (cache lengths, work items,
  *    page numbers) on the host and stages them through pinned memory that later calls reuse, and it may wait on an
- *    event of its own; on a capturing stream the call returns RS_EHIP.  A replay would also be meaningless: each call's
+ *    event of its own; on a capturing stream the call returns RS_ESTATE and records nothing.  A replay would also be meaningless: each call's
  *    shape depends on the cache lengths it finds.  Between the kernels of consecutive calls the stream idles for a few
  *    microseconds, so there is little for a graph to win.
  *  - Errors are decided on the host BEFORE anything is launched; on any status other than RS_OK

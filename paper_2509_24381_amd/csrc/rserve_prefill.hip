@@ -575,6 +575,11 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
                           const void* x, void* y, void* ws, void* stream, const int* positions3 = nullptr) {
     const rs_layer_cfg& f = ctx->cfg;
     const WorkspaceLayout L = ws_layout(ctx, T, R);
+    {   // a call recorded into a HIP graph would replay with stale descriptors: refuse it, before anything changes
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(reinterpret_cast<hipStream_t>(stream), &capturing) != hipSuccess) (void)hipGetLastError();
+        else if (capturing != hipStreamCaptureStatusNone) return fail(RS_ESTATE, "the stream is capturing a HIP graph");
+    }
 
     // ---- host descriptors
     std::vector<ReqDesc> reqs;

@@ -241,6 +241,39 @@ def test_export_import_round_trip_is_bit_exact():
         np.testing.assert_array_equal(r.to_numpy_f32(v2), v)
 
 
+def test_a_capturing_stream_is_refused_and_nothing_changes():
+    """Calls stage their descriptors through host memory that later calls reuse, so a recorded call would replay with
+    stale ones: on a stream that is capturing a HIP graph the library returns RS_ESTATE before it launches or changes
+    anything (a paged cache keeps its pages in the pool), and works as before once the capture is over."""
+    r = R()
+    from paper_2509_24381_amd.binding import RsError
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 61)
+    stack = r.LayerStack(shape, [w], max_tokens=128, max_requests=1, max_pos=512)
+    pool = stack.new_pool(4)
+    kv = pool.new_cache(1)
+    x = r.to_device_bf16(synth.prompt_rows([("text", 100)], shape.hidden, 62))
+    y = torch.empty_like(x)
+    stack.prefill_batch(0, [kv], [30], x[:30], y[:30])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    status = None
+    with torch.cuda.graph(g):
+        try:
+            stack.prefill_batch(0, [kv], [70], x[30:], y[30:])
+        except RsError as e:
+            status = e.status_name
+    assert status == "RS_ESTATE" and kv.length(0) == 30 and pool.free_pages == 3
+    y2 = stack.prefill_batch(0, [kv], [70], x[30:], y[30:])
+    torch.cuda.synchronize()
+    fresh = stack.new_cache(100)
+    y_ref = torch.empty_like(x)
+    stack.prefill_batch(0, [fresh], [30], x[:30], y_ref[:30])
+    stack.prefill_batch(0, [fresh], [70], x[30:], y_ref[30:])
+    torch.cuda.synchronize()
+    assert kv.length(0) == 100 and torch.equal(y, y_ref)
+
+
 @pytest.mark.parametrize("shape_name", ["small128", "wide_mlp"])
 def test_row_counts_around_every_wavefront_and_block_boundary(shape_name):
     """The GEMMs choose their geometry and the work of their wavefronts by the row count of the call: wavefronts whose 64
