@@ -584,7 +584,8 @@ def test_workload5_72b_32768_sampled_rows():
 
 
 # ------------------------------------------------------------------ split key ranges (few query rows, long cache)
-@pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 4500, 70), ("small128", 4200, 33), ("small128", 5000, 300)])
+@pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 4500, 70), ("small128", 4200, 33), ("small128", 5000, 300),
+                                                         ("tiny", 131000, 100)])
 def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_new):
     """A short chunk against a long cache gives fewer attention blocks than compute units; the library then cuts each
     block's key range into parts and merges them.  The result must meet the oracle's bar, and agree closely with the
@@ -600,6 +601,8 @@ def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_n
     y, caches = run_batch(shape, w, reqs, capacity=prior + 512)
     y_ref, caches_ref = oracle_batch(shape, w, reqs)
     check(f"{shape_name} split-range y (P={prior}, T={t_new})", y, y_ref)
+    if prior > 32768:   # (an average over 131000 random values is smaller than the bf16 rounding of y: nothing left to compare)
+        return
     w.wd = np.zeros_like(w.wd)            # and with the MLP off, so that the attention term is what is compared
     y, _ = run_batch(shape, w, reqs, capacity=prior + 512)
     y_ref, _ = oracle_batch(shape, w, reqs)
