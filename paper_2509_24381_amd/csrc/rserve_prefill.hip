@@ -639,8 +639,9 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
             for (int ax = 0; ax < 3; ++ax) rowpos.push_back(positions3 ? positions3[3 * (size_t)(row0 + t) + ax] : P + t);
         row0 += Ti;
     }
-    // Few blocks and long caches: cut the key ranges so that about two workgroups per compute unit exist (the default
-    // kernel only).  A part has at least ATT_MIN_PART_TILES tiles (8 would do for what follows), so every row of the block
+    // Few blocks and long caches: cut the key ranges so that up to two workgroups per compute unit exist, not more (a third
+    // round of workgroups costs more than the shorter parts save: 512 rows on 16384 cached tokens 201 us with 5 parts, 175
+    // with 4) - the default kernel only.  A part has at least ATT_MIN_PART_TILES tiles (8 would do for what follows), so every row of the block
     // sees keys in each part: the rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden
     // from some of them.
     std::vector<AttnMergeItem> mitems;
@@ -653,7 +654,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
             int longest = 0;
             for (const AttnItem& it : items) longest = std::max(longest, it.nkb);
             want = (blocks < ctx->n_cu && longest >= ATT_MIN_SPLIT_TILES)
-                       ? std::min(ATT_MAX_PARTS, (2 * ctx->n_cu + blocks - 1) / blocks) : 1;
+                       ? std::min(ATT_MAX_PARTS, std::max(1, 2 * ctx->n_cu / blocks)) : 1;
         }
         if (want > 1) {
             std::vector<AttnItem> cut;
