@@ -516,6 +516,79 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
             c_slot = n_slot;
         };
 
+        // The narrow geometry reads the weight fragments of a whole step one step ahead (all four k-steps of step s + 1
+        // behind the MFMAs of the second half of step s, right after the barrier that publishes them): with one or two
+        // units a k-step is 2 or 4 MFMAs, too few to cover the LDS latency of a read issued one k-step ahead, and the
+        // matrix pipe would wait for its operands four times per step.
+        constexpr bool FA = MAXNT == 2;
+        static_assert(!FA || XB % 2 == 0, "the two fragment sets alternate step by step");
+        bf16x8 wcA[4][NTW], wcB[4][NTW];
+        // (inline asm names only its own lambda's parameters: operands taken from an enclosing scope are not captured)
+        auto read_frag = [](auto offc, bf16x8& dst, const uint32_t addr) { RS_DS_READ_B128(dst, addr, decltype(offc)::value); };
+        auto read_step_frags = [&](bf16x8 (&wf)[4][NTW], const uint32_t slot) {
+            static_for<0, 4>([&](auto kc) {
+                static_for<0, NTW>([&](auto ic) {
+                    constexpr int kk = decltype(kc)::value, i = decltype(ic)::value;
+                    read_frag(std::integral_constant<int, i * WU * 4096>{}, wf[kk][i], aw[kk] + slot);
+                });
+            });
+        };
+        auto wait_step_frags = [&](bf16x8 (&wf)[4][NTW]) {   // "s_waitcnt lgkmcnt(0)" tied to the fragments it guards
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[0][0]));
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int i = 0; i < NTW; ++i) asm volatile("" : "+v"(wf[kk][i]));
+        };
+        // 2 NTW MFMAs of k-step KK with `count` memory operations riding behind them
+        auto phase_fa = [&](auto kkc, bf16x8 (&wf)[NTW], bf16x8 (&xc)[2][4], auto count, auto&& op) {
+            constexpr int KK = decltype(kkc)::value;
+            constexpr int LA = decltype(count)::value;
+            static_for<0, SL>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int i = q >> 1, j = q & 1;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xc[j][KK], acc[i][j], 0, 0, 0);
+                constexpr int o_lo = (LA <= SL) ? (q < LA ? q : LA) : (q * LA / SL);
+                constexpr int o_hi = (LA <= SL) ? (q + 1 < LA ? q + 1 : LA) : ((q + 1) * LA / SL);
+                static_for<o_lo, o_hi>([&](auto oc) { op(oc); });
+                RS_FENCE();
+            });
+        };
+        auto step_fa = [&](bf16x8 (&xc)[2][4], bf16x8 (&xn)[2][4], bf16x8 (&wc)[4][NTW], bf16x8 (&wn)[4][NTW]) {
+            const uint32_t n_slot = (c_slot + SLOT_BYTES) & (RING_BYTES - 1);
+            wait_step_frags(wc);
+            phase_fa(std::integral_constant<int, 0>{}, wc[0], xc, std::integral_constant<int, 4>{}, [&](auto ec) { load_x(ec, xn); });
+            phase_fa(std::integral_constant<int, 1>{}, wc[1], xc, std::integral_constant<int, 4>{},
+                     [&](auto ec) { load_x(std::integral_constant<int, decltype(ec)::value + 4>{}, xn); });
+            x_advance();
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 + (AHEAD - 2) * (NT + 8)) : "memory");   // (as in step)
+            asm volatile("s_barrier" ::: "memory");
+            RS_FENCE();
+            constexpr int W_A = (NT + 1) / 2, W_B = NT - W_A;
+            constexpr int RD = 2 * NTW;   // fragment reads per half: two k-steps of the next step
+            phase_fa(std::integral_constant<int, 2>{}, wc[2], xc, std::integral_constant<int, RD + W_A>{}, [&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                if constexpr (e < RD) read_frag(std::integral_constant<int, (e % NTW) * WU * 4096>{}, wn[e / NTW][e % NTW], aw[e / NTW] + n_slot);
+                else load_w(std::integral_constant<int, e - RD>{});
+            });
+            phase_fa(std::integral_constant<int, 3>{}, wc[3], xc, std::integral_constant<int, RD + W_B + 1>{}, [&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                if constexpr (e < RD) {
+                    read_frag(std::integral_constant<int, (e % NTW) * WU * 4096>{}, wn[2 + e / NTW][e % NTW], aw[2 + e / NTW] + n_slot);
+                } else if constexpr (e - RD < W_B) {
+                    load_w(std::integral_constant<int, e - RD + W_A>{});
+                } else {
+                    if (__builtin_expect(d_nt > NT, 0))   // the stream is in a wider tile: one more group of units
+                        static_for<0, WU>([&](auto gc) {
+                            constexpr int k = NT + decltype(gc)::value;
+                            load_w(std::integral_constant<int, k < MAXNT ? k : 0>{});
+                        });
+                    stream_advance();
+                }
+            });
+            c_slot = n_slot;
+        };
+
         // tile start: xbuf[0 .. XD - 1] hold (or are receiving) the tile's first token fragments; its first weight step was
         // published by the previous tile's last barrier (by the prologue for the first tile)
         asm volatile("s_barrier" ::: "memory");
@@ -540,22 +613,23 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
             }
             return;
         }
-        static_for<0, NTW>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
+        if constexpr (FA) read_step_frags(wcA, c_slot);
+        else static_for<0, NTW>([&](auto ic) { read_w(ic, wa, aw[0] + c_slot); });
         // step number s multiplies buffer s mod XB and loads the fragments of step s + XD into the buffer step s - 1 used
+        // (narrow geometry: even steps multiply fragment set A and read set B for the next step, odd steps the reverse)
+        auto do_step = [&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            if constexpr (!FA) step(xbuf[u], xbuf[(u + XD) % XB]);
+            else if constexpr (u % 2 == 0) step_fa(xbuf[u], xbuf[(u + XD) % XB], wcA, wcB);
+            else step_fa(xbuf[u], xbuf[(u + XD) % XB], wcB, wcA);
+        };
         int s = 0;
-        for (; s + XB <= ns; s += XB)
-            static_for<0, XB>([&](auto uc) {
-                constexpr int u = decltype(uc)::value;
-                step(xbuf[u], xbuf[(u + XD) % XB]);
-            });
+        for (; s + XB <= ns; s += XB) static_for<0, XB>([&](auto uc) { do_step(uc); });
         // the steps left over, then the fragments in flight move to where the next tile expects them (buffer 0 first)
         static_for<1, XB>([&](auto rc) {
             constexpr int R = decltype(rc)::value;
             if (ns - s == R) {
-                static_for<0, R>([&](auto uc) {
-                    constexpr int u = decltype(uc)::value;
-                    step(xbuf[u], xbuf[(u + XD) % XB]);
-                });
+                static_for<0, R>([&](auto uc) { do_step(uc); });
                 bf16x8 moved[XB][2][4];
 #pragma unroll
                 for (int b = 0; b < XD; ++b)      // (the buffer multiplied last holds nothing that is still needed)
@@ -571,7 +645,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
                         for (int kk = 0; kk < 4; ++kk) xbuf[b][j][kk] = moved[b][j][kk];
             }
         });
-        tie_wait_lgkm0<NTW>(wa);  // the look-ahead read behind the last step (discarded: the next tile reads its own)
+        // the look-ahead read behind the last step (discarded: the next tile reads its own)
+        if constexpr (FA) {
+            wait_step_frags(wcA);
+            wait_step_frags(wcB);
+        } else {
+            tie_wait_lgkm0<NTW>(wa);
+        }
         gemm_epilogue<EPI, NTW, WU>(a, acc, m0 + tw * 64, unit0 + uw, half, l32, split);
     };
 
