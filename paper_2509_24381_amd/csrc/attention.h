@@ -99,12 +99,13 @@ struct AttnItem {
 };
 
 // Split key ranges.  With few query rows and a long cache there are fewer blocks than compute units (a 256-token chunk
-// at the 7B shape gives 56), each walking the whole cache.  The host then cuts a block's tiles into up to 8 consecutive
+// at the 7B shape gives 56), each walking the whole cache.  The host then cuts a block's tiles into up to ATT_MAX_PARTS consecutive
 // parts, one workgroup each; a part leaves  O~ = sum_k 2^((s_k - m) c) v_k  (fp32, unnormalised), its reference maximum m
 // and its row sums l in a slot of the split buffer, and attn_merge_kernel combines the parts of a block:
 //   M = max_p m_p,  w_p = 2^((m_p - M) c),  out = sum_p w_p O~_p / sum_p w_p l_p.
 // A slot holds 128 rows: O~ as [D/4 chunks of 4 floats][128 rows] (the 32 lanes of a store cover 512 contiguous bytes),
 // then m[128], then l[128].
+constexpr int ATT_MAX_PARTS = 16;
 template <int D>
 struct AttnPartial {
     static constexpr int CHUNKS = D / 4;
@@ -632,8 +633,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const Re
     }
 }
 
-// Combines the parts of split blocks (see AttnPartial).  One workgroup per block: thread (row, c16) handles row `row` of
-// the block and the chunks c16, c16 + 2, ... of its D/4 chunks of 4 features.
+// Combines the parts of split blocks (see AttnPartial).  ATT_MERGE_Y workgroups per block (grid y): thread (row, c2) of
+// workgroup y handles row `row` of the block and the chunks 2y + c2, 2y + c2 + 2 ATT_MERGE_Y, ... of its D/4 chunks of 4
+// features - one or two chunks, so all of a thread's loads are in flight together (one workgroup per block walking its 16
+// chunks one after the other took 13 us, more than a short key range saves).  Every workgroup computes the rows' weights.
+constexpr int ATT_MERGE_Y = 8;
 struct AttnMergeItem {
     int req;
     int kvh;
@@ -654,27 +658,41 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const ReqDesc* __restri
     const int tok = row / g;
     const int head = item.kvh * g + (row - tok * g);
     const float* const base = split_buf + (size_t)item.slot0 * AttnPartial<D>::SLOT_FLOATS;
-    float m_all = -INFINITY;
-    for (int p = 0; p < item.n_parts; ++p) m_all = fmaxf(m_all, base[p * AttnPartial<D>::SLOT_FLOATS + (size_t)D * ATT_ROWS + rs]);
-    float l_all = 0.0f;
-    float w[8];  // at most 8 parts
+    // (all loads of a round are issued together: absent parts read as m = -inf, l = 0 and get weight 0)
+    float mp[ATT_MAX_PARTS], lp[ATT_MAX_PARTS];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        w[p] = 0.0f;
+    for (int p = 0; p < ATT_MAX_PARTS; ++p) {
+        mp[p] = -INFINITY;
+        lp[p] = 0.0f;
         if (p < item.n_parts) {
             const float* sp = base + p * AttnPartial<D>::SLOT_FLOATS;
-            w[p] = __builtin_amdgcn_exp2f((sp[(size_t)D * ATT_ROWS + rs] - m_all) * scale_log2e);
-            l_all += w[p] * sp[(size_t)(D + 1) * ATT_ROWS + rs];
+            mp[p] = sp[(size_t)D * ATT_ROWS + rs];
+            lp[p] = sp[(size_t)(D + 1) * ATT_ROWS + rs];
+        }
+    }
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < ATT_MAX_PARTS; ++p) m_all = fmaxf(m_all, mp[p]);
+    float l_all = 0.0f;
+    float w[ATT_MAX_PARTS];
+#pragma unroll
+    for (int p = 0; p < ATT_MAX_PARTS; ++p) {
+        w[p] = 0.0f;
+        if (p < item.n_parts) {
+            w[p] = __builtin_amdgcn_exp2f((mp[p] - m_all) * scale_log2e);
+            l_all += w[p] * lp[p];
         }
     }
     const float inv = 1.0f / l_all;
     const uint32_t m = (uint32_t)(rq.row0 + tok);
     char* const op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u;
     const int ks0 = (head * D) >> 4;
-    for (int c = c2; c < AttnPartial<D>::CHUNKS; c += 2) {
+    static_assert(AttnPartial<D>::CHUNKS % (2 * ATT_MERGE_Y) == 0, "chunks divide among the merge workgroups");
+#pragma unroll
+    for (int c = 2 * blockIdx.y + c2; c < AttnPartial<D>::CHUNKS; c += 2 * ATT_MERGE_Y) {
         f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int p = 0; p < 8; ++p)
+        for (int p = 0; p < ATT_MAX_PARTS; ++p)
             if (p < item.n_parts) {
                 const f32x4 o = *reinterpret_cast<const f32x4*>(base + p * AttnPartial<D>::SLOT_FLOATS + ((size_t)c * ATT_ROWS + rs) * 4);
 #pragma unroll

@@ -163,9 +163,8 @@ struct DescSizes {
     size_t reqs, items, vblocks, rowpos, pagetab, mitems, fp8, total;
 };
 
-constexpr int ATT_MAX_PARTS = 8;   // parts per block of a split key range
-constexpr int ATT_MIN_PART_TILES = 16;     // a part is worth a workgroup and its share of the merge from about 1000 keys
-constexpr int ATT_MIN_SPLIT_TILES = 64;    // no block of the call is split unless the longest walks at least 4096 keys
+constexpr int ATT_MIN_PART_TILES = 8;      // a part is worth a workgroup and its share of the merge from about 500 keys
+constexpr int ATT_MIN_SPLIT_TILES = 16;    // no block of the call is split unless the longest walks at least 1024 keys
 // slots of the split buffer: blocks are split only when there are fewer of them than compute units, into about two
 // workgroups per unit in total (sized for the 256 units of an MI355X; a block that finds no free slots stays whole)
 size_t attn_split_slots(const rs_ctx*) { return 768; }
@@ -385,7 +384,7 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     RS_HIP(hipGetLastError());
     if (n_mitems > 0) {
-        hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(n_mitems), dim3(256), 0, st, d_reqs, d_mitems, (const float*)split_buf, attn,
+        hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(n_mitems, ATT_MERGE_Y), dim3(256), 0, st, d_reqs, d_mitems, (const float*)split_buf, attn,
                            c->q_dim, c->group, scale_log2e);
         RS_HIP(hipGetLastError());
     }
@@ -639,18 +638,18 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
             for (int ax = 0; ax < 3; ++ax) rowpos.push_back(positions3 ? positions3[3 * (size_t)(row0 + t) + ax] : P + t);
         row0 += Ti;
     }
-    // Few blocks and long caches: cut the key ranges so that up to two workgroups per compute unit exist, not more (a third
-    // round of workgroups costs more than the shorter parts save: 512 rows on 16384 cached tokens 201 us with 5 parts, 175
-    // with 4) - the default kernel only.  A part has at least ATT_MIN_PART_TILES tiles (8 would do for what follows), so every row of the block
-    // sees keys in each part: the rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden
-    // from some of them.
+    // Fewer blocks than compute units: cut the key ranges so that up to two workgroups per compute unit exist, not more (a
+    // third round of workgroups costs more than the shorter parts save: 512 rows on 16384 cached tokens 201 us with 5 parts,
+    // 175 with 4) - the default kernel only.  A part has at least ATT_MIN_PART_TILES tiles, so every row of the block sees
+    // keys in each part: the rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden from
+    // some of them.
     std::vector<AttnMergeItem> mitems;
     if (ctx->attn_variant == 1 && !items.empty()) {
         const int blocks = (int)items.size();
         int want = ctx->attn_split;
         if (want == 0) {
-            // (the merge is a second kernel: about 10 us with its launch, which short key ranges do not win back - a
-            // 512-row chunk on a 2048-token prompt is faster unsplit)
+            // (the merge is a second kernel of a few microseconds; measured at the 7B shape, 64 rows on 2048 cached tokens:
+            // 43 us of attention unsplit, 25 in 4 parts; 512 rows on 1536: 50 -> 40; below 1024 keys nothing is gained)
             int longest = 0;
             for (const AttnItem& it : items) longest = std::max(longest, it.nkb);
             want = (blocks < ctx->n_cu && longest >= ATT_MIN_SPLIT_TILES)

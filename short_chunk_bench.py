@@ -71,7 +71,7 @@ def main():
         print(f"| {t_rows} | {prior} | - | {a1:.0f} | - | {c1:.0f} |", flush=True)
     if cases:
         return
-    for t_rows, prior in ((64, 8192), (256, 8192), (256, 32768), (256, 131072), (512, 16384), (1024, 8192), (2048, 6144)):
+    for t_rows, prior in ((64, 2048), (512, 1536), (64, 8192), (256, 8192), (256, 32768), (256, 131072), (512, 16384), (1024, 8192), (2048, 6144)):
         a0, c0 = time_case(shape, w, t_rows, prior, "1", args.reps)
         a1, c1 = time_case(shape, w, t_rows, prior, None, args.reps)
         print(f"| {t_rows} | {prior} | {a0:.0f} | {a1:.0f} | {c0:.0f} | {c1:.0f} |", flush=True)

@@ -585,10 +585,10 @@ def test_workload5_72b_32768_sampled_rows():
 
 # ------------------------------------------------------------------ split key ranges (few query rows, long cache)
 @pytest.mark.parametrize("shape_name, prior, t_new", [("tiny", 4500, 70), ("small128", 4200, 33), ("small128", 5000, 300),
-                                                         ("tiny", 131000, 100)])
+                                                         ("small128", 1100, 40), ("tiny", 2000, 64), ("tiny", 131000, 100)])
 def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_new):
-    """A short chunk against a long cache gives fewer attention blocks than compute units; the library then cuts each
-    block's key range into parts and merges them.  The result must meet the oracle's bar, and agree closely with the
+    """A short chunk against a cache of more than about a thousand tokens gives fewer attention blocks than compute units;
+    the library then cuts each block's key range into parts (2 in the shortest case here, 16 in the longest) and merges them.  The result must meet the oracle's bar, and agree closely with the
     unsplit kernel (RS_ATTN_SPLIT=1 in a child process would be the same code path as large chunks take: here the two
     are compared through the oracle)."""
     shape = synth.TINY if shape_name == "tiny" else synth.LayerShape("small128", 256, 4, 2, 128, 512)
