@@ -648,12 +648,24 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         const int blocks = (int)items.size();
         int want = ctx->attn_split;
         if (want == 0) {
-            // (the merge is a second kernel of a few microseconds; measured at the 7B shape, 64 rows on 2048 cached tokens:
-            // 43 us of attention unsplit, 25 in 4 parts; 512 rows on 1536: 50 -> 40; below 1024 keys nothing is gained)
+            // (the merge is a second kernel of about 6 us, i.e. six tiles of a block's walk; measured at the 7B shape, 64 rows
+            // on 2048 cached tokens: 43 us of attention unsplit, 25 in 4 parts; 512 rows on 1536: 50 -> 40)
             int longest = 0;
             for (const AttnItem& it : items) longest = std::max(longest, it.nkb);
             want = (blocks < ctx->n_cu && longest >= ATT_MIN_SPLIT_TILES)
                        ? std::min(ATT_MAX_PARTS, std::max(1, 2 * ctx->n_cu / blocks)) : 1;
+            if (want > 1) {
+                // What the call's longest walk would shrink by, in tiles (blocks under two parts' worth stay whole and may
+                // then be the longest).  Splitting pays from 7 tiles when the chip is nearly empty and from 12 when the
+                // blocks alone nearly fill it (fitted: 1024 rows on 512 cached tokens lose 1 us with a gain of 9 tiles, on
+                // 1024 cached tokens they win 6 us with a gain of 16; 64 rows on 960 win 6 us with a gain of 8).
+                int longest_after = 0;
+                for (const AttnItem& it : items) {
+                    const int parts = std::min(want, it.nkb / ATT_MIN_PART_TILES);
+                    longest_after = std::max(longest_after, parts < 2 ? it.nkb : (it.nkb + parts - 1) / parts);
+                }
+                if ((long)(longest - longest_after) * ctx->n_cu < 7L * ctx->n_cu + 5L * blocks) want = 1;
+            }
         }
         if (want > 1) {
             std::vector<AttnItem> cut;
