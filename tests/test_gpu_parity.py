@@ -608,3 +608,33 @@ def test_short_chunk_on_a_long_cache_splits_the_key_range(shape_name, prior, t_n
     y_ref, _ = oracle_batch(shape, w, reqs)
     h = t_new // 2   # (text rows only: on image rows the bf16 rounding of y is as large as the attention term itself)
     check(f"{shape_name} split-range attention term", (y - rows)[h:], (y_ref - rows)[h:], tol=2e-2)
+
+
+def test_ragged_batch_with_whole_and_split_key_ranges_in_one_call():
+    """Four requests in one call whose blocks fall on both sides of the split rule: caches of 3000 and 1500 tokens (their
+    blocks are cut into 6 and 3 parts), of 900 tokens and an empty one (too short for two parts: left whole).  Outputs and
+    caches of every request meet the oracle's bar; with the MLP off the attention term does too, request by request."""
+    shape = synth.LayerShape("small128", 256, 4, 2, 128, 512)
+    w = synth.layer_weights(shape, 71, gains="uniform")
+    rng = np.random.default_rng(72)
+    reqs = []
+    for i, (prior, t_new) in enumerate([(3000, 40), (0, 70), (900, 33), (1500, 128)]):
+        pk = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+        pv = synth.bf16_round(rng.standard_normal((prior, shape.n_kv_heads, shape.head_dim), dtype=np.float32))
+        rows = synth.prompt_rows([("text", t_new)], shape.hidden, 73 + i)
+        reqs.append(synth.BatchRequest(prior, pk, pv, rows))
+    y, caches = run_batch(shape, w, reqs, capacity=3200)
+    y_ref, caches_ref = oracle_batch(shape, w, reqs)
+    check("mixed split batch y", y, y_ref)
+    for i, ((k, v), (k_ref, v_ref)) in enumerate(zip(caches, caches_ref)):
+        check(f"mixed split batch K of request {i}", k, k_ref)
+        check(f"mixed split batch V of request {i}", v, v_ref)
+    w.wd = np.zeros_like(w.wd)
+    y, _ = run_batch(shape, w, reqs, capacity=3200)
+    y_ref, _ = oracle_batch(shape, w, reqs)
+    x = np.concatenate([r.rows for r in reqs], axis=0)
+    off = 0
+    for i, r in enumerate(reqs):
+        n = r.rows.shape[0]
+        check(f"mixed split batch attention term of request {i}", (y - x)[off: off + n], (y_ref - x)[off: off + n], tol=2e-2)
+        off += n
