@@ -210,7 +210,12 @@ double gemm_cost_clocks(const rs_ctx* c, int M, int units, int k_steps, int spli
     const int ntiles = (ups + GS_MAX_NT - 1) / GS_MAX_NT;
     const double nt = (double)ups / ntiles;
     const int steps = (k_steps + splits - 1) / splits;
-    double clocks = (double)waves * ntiles * (steps * (256.0 * nt + 350.0) + 20000.0);
+    // (a step of the wide geometry also moves 32 KB of token fragments per workgroup whatever the tile's width: with three
+    // units or fewer that, not the MFMAs, sets its duration - about 1200 clocks measured; without this floor calls of 257
+    // to 768 rows kept the O projection unsplit, 3 to 8 us slower than in two or three K ranges)
+    double step = 256.0 * nt + 350.0;
+    if (!use_narrow(c, tiles_m, splits, units)) step = std::max(step, 1200.0);
+    double clocks = (double)waves * ntiles * (steps * step + 20000.0);
     if (splits > 1) clocks += (double)M * units * 32.0 * (4.0 * splits + 4.0) / 2.0e12 * 1.4e9;
     return clocks;
 }
