@@ -198,7 +198,12 @@ rs_status rs_kv_alloc_paged_fp8(rs_ctx* ctx, rs_kv_pool* pool, int n_layers, flo
  *   y   device bf16 [T, H]: layer output; may alias x.
  * With P = rs_kv_len(kv, layer): rows take positions P..P+T-1, their post-RoPE K and V are appended at [P, P+T),
  * row i attends to cache entries 0..P+i, and the layer's length becomes P+T.  T = 0 is a no-op.
- * RS_ECAPACITY if P+T exceeds the cache capacity or max_pos; RS_EINVAL if T > max_tokens_per_call. */
+ * RS_ECAPACITY if P+T exceeds the cache capacity or max_pos; RS_EINVAL if T > max_tokens_per_call.
+ * Reproducibility: every kernel divides its work in a way fixed by the call's sizes and none uses atomics, so the same
+ * call on the same inputs gives the same bits.  The K and V a token leaves in the cache are the same bits however its
+ * prompt is cut into chunks or batched with other requests (the QKV projection is never split along K, and the row sums
+ * of the norm before it are taken in one fixed order).  A token's output row may differ between chunkings by rounding:
+ * the K ranges of the residual projections and the key ranges of the attention blocks are chosen per call. */
 rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv,
                            const void* x_dev, int T, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
