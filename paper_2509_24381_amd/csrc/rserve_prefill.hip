@@ -193,8 +193,8 @@ int strips_for(const rs_ctx* c, int tiles_m, int splits, int units) {
 }
 
 // Whether a launch qualifies for the narrow kernel geometry: few token blocks, no strip wider than the narrow tile.
-bool use_narrow(const rs_ctx* c, int tiles_m, int splits, int units) {
-    if (!c->gemm_narrow || tiles_m > c->narrow_max_tiles_m) return false;
+bool use_narrow(const rs_ctx* c, int tiles_m, int splits, int units, int max_tiles_m = 0) {
+    if (!c->gemm_narrow || tiles_m > std::max(max_tiles_m, c->narrow_max_tiles_m)) return false;
     const int strips = strips_for(c, tiles_m, splits, units);
     return (units + strips - 1) / strips <= GS_NARROW_NT;
 }
@@ -293,7 +293,9 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
     }
     a.strips = strips_for(c, a.tiles_m, splits, units);
     dim3 grid(a.tiles_m * a.strips, splits);
-    if (use_narrow(c, a.tiles_m, splits, units))
+    // (the QKV projection, which is never split along K, also takes the narrow geometry on two token blocks: 43 -> 38 us
+    // at 320 rows, no change at 512; the residual projections of such calls are better off split along K in the wide one)
+    if (use_narrow(c, a.tiles_m, splits, units, EPI == EPI_QKV_ROPE ? 2 : 0))
         hipLaunchKernelGGL((gemm_strip_kernel<EPI, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD>), grid, dim3(256),
                            GS_NARROW_LDS_BYTES, st, a);
     else
