@@ -214,12 +214,16 @@ def layer_forward(x: np.ndarray, p: LayerParams, positions3: Optional[np.ndarray
     return y, k, v
 
 
-def layer_forward_rows(x: np.ndarray, p: LayerParams, rows: Sequence[int]):
+def layer_forward_rows(x: np.ndarray, p: LayerParams, rows: Sequence[int], row_block: int = 512):
     """The same definition evaluated for selected output rows only.
 
     The K~/V cache is still produced for every token (a row's attention needs all earlier
     keys), but queries, attention, the output projection and the MLP are evaluated only for
-    `rows`.  Returns (Y[rows], K~[N], V[N]).  Used where the full layer is too slow to run whole.
+    `rows` (any order, output in the same order).  Returns (Y[rows], K~[N], V[N]).  Used where the
+    full layer is too slow to run whole.  As in `causal_gqa_attention`, the selected rows are
+    taken in slabs of `row_block` only to bound memory and time: a slab's scores are formed
+    against every key up to the slab's latest position, keys after a row's own position are
+    set to -inf, and each row's softmax is taken over its full visible key range in one go.
     """
     x = np.asarray(x, dtype=F64)
     n = x.shape[0]
@@ -238,12 +242,17 @@ def layer_forward_rows(x: np.ndarray, p: LayerParams, rows: Sequence[int]):
     qs = rope(qs.reshape(len(rows), p.n_q_heads, p.head_dim), rows, p.rope_theta)
     scale = 1.0 / np.sqrt(F64(p.head_dim))
     o = np.empty((len(rows), p.n_q_heads, p.head_dim), dtype=F64)
-    for i, t in enumerate(rows.tolist()):
+    by_position = np.argsort(rows, kind="stable")     # slabs of neighbouring positions waste the fewest masked keys
+    for a in range(0, len(rows), row_block):
+        sel = by_position[a: a + row_block]
+        pos = rows[sel]
+        t_end = int(pos.max()) + 1
+        visible = np.arange(t_end)[None, :] <= pos[:, None]
         for hh in range(p.n_q_heads):
             c = hh // p.group
-            s = (k[: t + 1, c, :] @ qs[i, hh, :]) * scale
-            a = _softmax_rows(s[None, :])[0]
-            o[i, hh, :] = a @ v[: t + 1, c, :]
+            s = (qs[sel, hh, :] @ k[:t_end, c, :].T) * scale
+            s = np.where(visible, s, -np.inf)
+            o[sel, hh, :] = _softmax_rows(s) @ v[:t_end, c, :]
     r = x[rows] + o.reshape(len(rows), -1) @ p.wo.T
     return _mlp_residual(r, p), k, v
 

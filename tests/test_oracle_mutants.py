@@ -104,6 +104,24 @@ def project_qkv_swaps_k_and_v(h, p):
 
 _orig_project = dl._project_qkv
 
+
+def _rows_form_variant(old, new):
+    """layer_forward_rows with one expression of its source replaced (the planted mistake)."""
+    import inspect
+    src = inspect.getsource(dl.layer_forward_rows)
+    assert src.count(old) == 1, old
+    scope = dict(vars(dl))
+    exec(src.replace(old, new), scope)
+    fn = scope["layer_forward_rows"]
+    fn.__name__ = "rows_form_" + "".join(ch if ch.isalnum() else "_" for ch in new)[:40]
+    return fn
+
+
+rows_form_strict_mask = _rows_form_variant("<= pos[:, None]", "< pos[:, None]")
+rows_form_sorted_output = _rows_form_variant("o[sel, hh, :] =", "o[np.arange(a, a + len(sel)), hh, :] =")
+rows_form_wrong_kv_head = _rows_form_variant("c = hh // p.group", "c = hh % p.n_kv_heads")
+rows_form_query_position = _rows_form_variant("p.head_dim), rows, p.rope_theta)", "p.head_dim), np.arange(len(rows)), p.rope_theta)")
+
 MUTANTS = [
     ("rope", rope_wrong_sign), ("rope", rope_interleaved_pairs), ("rope_angles", rope_angles_wrong_exponent),
     ("rmsnorm", rmsnorm_eps_outside), ("rmsnorm", rmsnorm_subtracts_mean), ("silu", silu_as_sigmoid),
@@ -112,6 +130,8 @@ MUTANTS = [
     ("causal_gqa_attention", attn_head_modulo),
     ("_mlp_residual", mlp_swapped_gate_up), ("_mlp_residual", mlp_without_residual),
     ("_mlp_residual", mlp_norm_gain_of_first_norm), ("_project_qkv", project_qkv_swaps_k_and_v),
+    ("layer_forward_rows", rows_form_strict_mask), ("layer_forward_rows", rows_form_sorted_output),
+    ("layer_forward_rows", rows_form_wrong_kv_head), ("layer_forward_rows", rows_form_query_position),
 ]
 
 PIN_CALLS = [
@@ -130,6 +150,7 @@ PIN_CALLS = [
     lambda: pins.test_layer_residual_special_cases(),
     lambda: pins.test_chunked_equals_unchunked(1),
     lambda: pins.test_chunk_attention_matches_scalar_loops_with_prefix(),
+    lambda: pins.test_rows_form_equals_full_form(),
 ]
 
 

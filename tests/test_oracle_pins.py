@@ -291,6 +291,11 @@ def test_rows_form_equals_full_form():
     np.testing.assert_allclose(yr, y[rows], atol=1e-12)
     np.testing.assert_allclose(kr, k, atol=1e-13)
     np.testing.assert_allclose(vr, v, atol=1e-13)
+    # every row, out of order and with a repeat, in slabs of 1, 4 and all at once: the slabs only bound memory
+    rows = list(rng.permutation(29)) + [5]
+    for row_block in (1, 4, 64):
+        yr, _, _ = layer_forward_rows(x, p, rows, row_block=row_block)
+        np.testing.assert_allclose(yr, y[rows], atol=1e-12)
 
 
 # ------------------------------------------------------------------ chunking / batching (section 2.2.1, Algorithm 2)
