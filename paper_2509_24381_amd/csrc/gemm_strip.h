@@ -123,6 +123,11 @@ RS_DEVICE u32x4 pair_runs(bf16x4 even_run, bf16x4 odd_run) {
 // unit unit0 + i.  Per-row inputs and all outputs go through buffer resources sized to M rows, so lanes whose token lies
 // past M read zeros and store nothing without any divergent branch (a divergent branch here, inside the tile loop, makes
 // the compiler keep the whole pipeline's scalar state in vector registers).
+// The accumulators live in accumulation registers, which the vector ALU cannot read.  Left alone, the register allocator
+// copies all of a token block's tiles (up to 128 registers) into vector registers at the top of the epilogue and spills
+// the pipeline's in-flight fragments to scratch memory to make room (about 100 dwords per lane and tile, written and read
+// back).  The empty asm statement at the top of each unit's iteration pins that unit's tile in accumulation registers up to
+// there, so the copies are made 16 registers at a time and nothing spills.
 template <int EPI, int NT, int USTRIDE = 1>
 RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base, int unit0, int half, int l32, int split) {
     constexpr int RSRC_FLAGS = 0x00020000;
@@ -139,6 +144,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             const uint32_t oblk = (uint32_t)(m >> 5) * (uint32_t)(a.ldo >> 4) * 1024u + (uint32_t)l32 * 16u + (uint32_t)half * 512u;
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
+                asm volatile("" : "+a"(acc[i][j]));
                 bf16x4 o[2];
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
@@ -161,6 +167,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             const uint32_t orow = (uint32_t)m * (uint32_t)a.ldo * 2u;
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
+                asm volatile("" : "+a"(acc[i][j]));
                 const int gu = unit0 + i * USTRIDE;
                 if (gu * 32 < a.rope_cols) {
                     // rows 0..15 of the unit are features f..f+15 of the head's first half, rows 16..31 their partners
@@ -242,6 +249,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                 __builtin_amdgcn_make_buffer_rsrc((void*)a.rowss, 0, a.rowss != nullptr ? a.M * (a.N >> 5) * 4 : 0, RSRC_FLAGS);
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
+                asm volatile("" : "+a"(acc[i][j]));
                 float ss = 0.0f;
                 bf16x4 o[4];
 #pragma unroll
