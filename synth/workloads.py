@@ -220,6 +220,10 @@ class Workload:
     def chunks(self) -> List[Tuple[int, int]]:
         return chunk_schedule(self.n_tokens, self.budget)
 
+    def text_row_mask(self) -> np.ndarray:
+        """True for the prompt rows that are text-token embeddings (the small-magnitude rows)."""
+        return np.concatenate([np.full(n, kind == "text") for kind, n in self.segments])
+
     def batch(self) -> List[BatchRequest]:
         """Workload 4: 16 requests, prior cache lengths U{0..max_prior}, chunk lengths Dirichlet(1)."""
         assert self.n_requests > 0
