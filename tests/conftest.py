@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the HIP library)")
+    config.addinivalue_line("markers", "sanitizer: builds the library with ASan + UBSan on its host code and re-runs the "
+                                       "host-only tests against it in a child process (about a minute of compile time)")
 
 
 def pytest_collection_modifyitems(config, items):
