@@ -9,8 +9,15 @@ A step is one pass of the whole hot path over the benchmark workload: a syntheti
 rs_prefill_batch, 5 = the 72B-shaped layer over a 32768-token prompt); the default, 3, is the headline configuration.
 
 Prints ONE JSON line (see README / DESIGN for the fields): metric, value, ms_per_step, roofline of the dominant
-kernel (the fused gate/up + SwiGLU GEMM, timed live with HIP events on its own stream inside the timed region), and
-the fp64 CPU oracle timed on a bounded sample of the same workload.
+kernel (the fused gate/up + SwiGLU GEMM, timed live with HIP events on its own stream inside the timed region), the
+attention step's TFLOP/s and KV-read GB/s (one extra sampled pass after the timed region), and the fp64 CPU oracle
+timed on a bounded sample of the same workload.
+
+Two side studies share the harness (they print their own tables / lines, not the benchmark line):
+  --short-chunks   one 7B-shaped layer call for short chunks on long caches, with and without split key ranges
+                   (what Algorithm 2 produces late in a long prompt); --case ROWS,CACHED restricts it to given pairs
+  --ttft           time to first token of one multimodal request against the embedding batch size C of Algorithm 1
+                   (section 3.2 / the embedding-batch-size study of section 4.3), stand-in encoder on a second stream
 """
 from __future__ import annotations
 
@@ -26,10 +33,13 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
-# Bytes crossing the L2 / fabric boundary per gate/up GEMM launch at T=2048 on the 7B shape, from the two rocprofv3 --pmc
-# passes summarised in profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
-# factors a plain copy kernel of known size gives).  Algorithmic bytes of the same launch: 363.9e6.
-GATE_UP_TRAFFIC_BYTES = (466051.5 * 2.0 + 151296.0 * 1.0) * 1024
+# Bytes crossing the L2 / fabric boundary per gate/up GEMM launch at T=2048 on the 7B shape: FETCH_SIZE and WRITE_SIZE
+# (KiB per dispatch) from the two rocprofv3 --pmc passes summarised, with their date and commands, in
+# profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md, each scaled by what the same counter reads for a plain copy kernel
+# of known size (--copy-calibration).  Algorithmic bytes of the same launch: 363.9e6.
+GATE_UP_FETCH_KIB, GATE_UP_FETCH_SCALE = 466051.5, 2.0
+GATE_UP_WRITE_KIB, GATE_UP_WRITE_SCALE = 151296.0, 1.0
+GATE_UP_TRAFFIC_BYTES = (GATE_UP_FETCH_KIB * GATE_UP_FETCH_SCALE + GATE_UP_WRITE_KIB * GATE_UP_WRITE_SCALE) * 1024
 
 
 def cpu_baseline(wl, w0, x, target_seconds: float):
@@ -67,6 +77,110 @@ def cpu_baseline(wl, w0, x, target_seconds: float):
                       f"{flops(rows) / dt / 1e9:.1f} GFLOP/s"}
 
 
+def short_chunk_case(shape, w, t_rows, prior, split_env, reps):
+    """(attention us, whole layer call us) of one call of t_rows rows on `prior` cached tokens; split_env "1" forbids
+    split key ranges, None leaves the choice to the library (the hook is read once, when the context is created)."""
+    import torch
+    from paper_2509_24381_amd import runner
+    if split_env is None:
+        os.environ.pop("RS_ATTN_SPLIT", None)
+    else:
+        os.environ["RS_ATTN_SPLIT"] = split_env
+    stack = runner.LayerStack(shape, [w], max_tokens=t_rows, max_requests=1, max_pos=prior + t_rows)
+    kv = stack.new_cache(prior + t_rows)
+    g = torch.Generator(device="cuda").manual_seed(20250924)
+    k = torch.randn(prior, shape.n_kv_heads, shape.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+    v = torch.randn(prior, shape.n_kv_heads, shape.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+    kv.import_(0, k, v)
+    x = torch.randn(t_rows, shape.hidden, device="cuda", generator=g).to(torch.bfloat16)
+    y = torch.empty_like(x)
+
+    def call():
+        kv.truncate(0, prior)
+        stack.prefill_batch(0, [kv], [t_rows], x, y)
+
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    stack.ctx.profile_enable("attention", reps)
+    for _ in range(reps):
+        call()
+    torch.cuda.synchronize()
+    ms, n = stack.ctx.profile_read()
+    stack.ctx.profile_enable(None)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return ms / n * 1e3, e0.elapsed_time(e1) / reps * 1e3
+
+
+def short_chunks(args):
+    """Markdown table: one row per (chunk rows, cached tokens) pair.  Synthetic inputs (N(0,1) cache content and rows,
+    N(0, 0.02) weights), resident; HIP events on the call's stream."""
+    import synth
+    cases = [tuple(int(v) for v in c.split(",")) for c in args.case]
+    if any(len(c) != 2 or c[0] < 1 or c[1] < 0 for c in cases):
+        sys.exit("--case takes ROWS,CACHED with ROWS >= 1 and CACHED >= 0")
+    shape = synth.L7B
+    w = synth.layer_weights(shape, 1)
+    print("| chunk rows | cached tokens | attention us, whole key range per block | attention us, split | layer call us, whole | layer call us, split |")
+    print("|---:|---:|---:|---:|---:|---:|")
+    for t_rows, prior in cases:   # given pairs: the default configuration only (the form a kernel trace is taken with)
+        a1, c1 = short_chunk_case(shape, w, t_rows, prior, None, args.reps)
+        print(f"| {t_rows} | {prior} | - | {a1:.0f} | - | {c1:.0f} |", flush=True)
+    if cases:
+        return
+    for t_rows, prior in ((64, 2048), (512, 1536), (64, 8192), (256, 8192), (256, 32768), (256, 131072), (512, 16384), (1024, 8192), (2048, 6144)):
+        a0, c0 = short_chunk_case(shape, w, t_rows, prior, "1", args.reps)
+        a1, c1 = short_chunk_case(shape, w, t_rows, prior, None, args.reps)
+        print(f"| {t_rows} | {prior} | {a0:.0f} | {a1:.0f} | {c0:.0f} | {c1:.0f} |", flush=True)
+
+
+def ttft_study(args):
+    """One JSON line per embedding batch size C: the benchmark prompt through `--layers` 7B-shaped layers (the 4 synthetic
+    ones reused cyclically: same cost as distinct weights, 1/7 of the memory); C = the whole request reproduces systems
+    that encode everything before the prefill starts (no overlap)."""
+    import torch
+    import synth
+    from paper_2509_24381_amd import pipeline, runner
+    wl = synth.workload(3)
+    weights = [wl.weights(l) for l in range(wl.n_layers)]
+    stack = runner.LayerStack(wl.shape, weights, max_tokens=args.budget, max_requests=1, max_pos=wl.n_tokens)
+    del weights
+    stack.layers = [stack.layers[l % wl.n_layers] for l in range(args.layers)]
+    segments = [(kind == "image", n) for kind, n in wl.segments]
+    rows = runner.to_device_bf16(wl.prompt())
+    enc = pipeline.StubEncoder(args.encoder_gflop_per_token)
+    head = None
+    if args.vocab > 0:
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        head = (torch.ones(wl.shape.hidden, device="cuda", dtype=torch.bfloat16),
+                (torch.randn(args.vocab, wl.shape.hidden, device="cuda", generator=gen) * 0.02).to(torch.bfloat16))
+    n_mm = sum(n for mm, n in segments if mm)
+    for c in args.batch_sizes:
+        times, enc_times, res = [], [], None
+        for rep in range(args.repeats + 1):
+            res, kv, out = pipeline.run_intra_request_pipeline(stack, segments, rows, min_tokens=c, token_budget=args.budget,
+                                                               encoder=enc, head=head)
+            if rep:                      # the first repetition warms up
+                times.append(res.ttft_ms)
+                enc_times.append(res.encode_ms)
+            del kv, out
+        times.sort()
+        print(json.dumps({"metric": "time to first token of one request (" + ("first token on the host" if head else "prefill complete")
+                                    + "), intra-request pipeline",
+                          "embedding_batch_size": "whole request" if c >= n_mm else c,
+                          "ttft_ms_median": times[len(times) // 2], "ttft_ms_min": times[0],
+                          "encode_done_ms_median": sorted(enc_times)[len(enc_times) // 2],
+                          "encode_batches": res.n_encode_batches, "prefill_rounds": res.n_rounds,
+                          "prompt_tokens": wl.n_tokens, "multimodal_tokens": n_mm, "layers": args.layers,
+                          "token_budget": args.budget, "encoder_gflop_per_token": args.encoder_gflop_per_token,
+                          "vocab": args.vocab, "first_token": res.first_token}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +197,20 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain 256 MiB elementwise copy kernel (torch.mul(a, 1, out=b)); "
                          "gives the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs a kernel of known traffic to scale by")
+    side = ap.add_argument_group("side studies (print their own output instead of the benchmark line)")
+    side.add_argument("--short-chunks", action="store_true", help="short chunks on long caches, 7B shape (markdown table)")
+    side.add_argument("--reps", type=int, default=20, help="--short-chunks: timed repetitions per case")
+    side.add_argument("--case", action="append", default=[], metavar="ROWS,CACHED",
+                      help="--short-chunks: only this (chunk rows, cached tokens) pair, default configuration only; repeatable")
+    side.add_argument("--ttft", action="store_true", help="time to first token against the embedding batch size C of Algorithm 1")
+    side.add_argument("--encoder-gflop-per-token", type=float, default=4.0, help="--ttft: cost of the stand-in encoder per multimodal token")
+    side.add_argument("--layers", type=int, default=28, help="--ttft: decoder layers the prefill runs through")
+    side.add_argument("--budget", type=int, default=2048, help="--ttft: token budget of a prefill round")
+    side.add_argument("--vocab", type=int, default=152064,
+                      help="--ttft: rows of the vocabulary matrix of the first-token head (inside the measured time); 0 stops the "
+                           "clock when the prefill is complete")
+    side.add_argument("--repeats", type=int, default=5, help="--ttft: timed repetitions per batch size")
+    side.add_argument("--batch-sizes", type=int, nargs="*", default=[256, 512, 1024, 2048, 4096, 1 << 30], help="--ttft: values of C")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -96,6 +224,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.short_chunks:
+        return short_chunks(args)
+    if args.ttft:
+        return ttft_study(args)
     wl = synth.workload(args.workload)
     sh = wl.shape
     weights = [wl.weights(l) for l in range(wl.n_layers)]
@@ -195,19 +327,24 @@ def main():
                      "avg_ms": gu_avg_ms, "launches": gu_n},
     }
 
+    # one more pass per measured step of the layer, outside the timed region, every launch of that step bracketed by HIP
+    # events on its stream: the attention step always (its TFLOP/s and the rate at which it reads the cached K and V),
+    # every step with --breakdown
+    bd = {}
+    for name in (STEPS if args.breakdown else ("attention",)):
+        stack.ctx.profile_enable(name, calls_per_step)
+        step()
+        torch.cuda.synchronize()
+        ms, n = stack.ctx.profile_read()
+        bd[name] = ms / max(n, 1)
+    stack.ctx.profile_enable(None)
     if args.breakdown:
-        bd = {}
-        for name in STEPS:
-            stack.ctx.profile_enable(name, calls_per_step)
-            step()
-            torch.cuda.synchronize()
-            ms, n = stack.ctx.profile_read()
-            bd[name] = ms / max(n, 1)
-        stack.ctx.profile_enable(None)
         out["breakdown_avg_ms_per_call"] = bd
-        attn_s = bd["attention"] * 1e-3 * calls_per_step
-        out["attention"] = {"avg_ms": bd["attention"], "tflops": attn_flops_step / attn_s / 1e12,
-                            "kv_read_GBps": kv_bytes_step / attn_s / 1e9, "kv_read_frac_of_hbm_peak": kv_bytes_step / attn_s / 1e9 / HBM_PEAK_GBS}
+    attn_s = bd["attention"] * 1e-3 * calls_per_step
+    out["attention"] = {"kernel": "append_kv_kernel is not included; attn_prefill_pipelined_kernel (+ attn_merge_kernel when key ranges are split)",
+                        "avg_ms": bd["attention"], "tflops": attn_flops_step / attn_s / 1e12,
+                        "frac_of_mfma_peak": attn_flops_step / attn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                        "kv_read_GBps": kv_bytes_step / attn_s / 1e9, "kv_read_frac_of_hbm_peak": kv_bytes_step / attn_s / 1e9 / HBM_PEAK_GBS}
 
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written

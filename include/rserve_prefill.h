@@ -93,7 +93,15 @@ typedef struct rs_kv rs_kv;   /* one request's KV cache over n_layers layers; ho
  * Allocates the RoPE cos/sin table (max_pos * d/2 * 8 bytes of device memory) and pinned staging for
  * per-call request descriptors.  RS_EINVAL if the shape is outside what the kernels support (see rs_layer_cfg).
  * On a host without a GPU the context is still created (host-only): every argument check works, and any call that
- * would have to launch returns RS_EHIP. */
+ * would have to launch returns RS_EHIP.
+ * TEST-ONLY environment variables, read once here.  They force launch shapes that the default rules pick only on other
+ * call sizes, so that the parity tests reach every kernel path on small inputs; results meet the same bar, speed does
+ * not.  Not for production use, and they may change without notice:
+ *   RS_SPLITK=n      K ranges of the residual projections (1..4; default: a cost model per call)
+ *   RS_NCU=n         compute-unit count the GEMM strips are sized for (default: the device's)
+ *   RS_NARROW=0      never the GEMM geometry for strips of at most two units;  RS_NARROW_TM=n  use it up to n token blocks
+ *   RS_PAIRS=0       never two wavefronts per pair of units in that geometry
+ *   RS_ATTN_SPLIT=n  parts every attention block's key range is cut into (1 = never; default: decided per call) */
 rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out);
 void rs_ctx_destroy(rs_ctx* ctx);
 
@@ -140,7 +148,12 @@ rs_status rs_kv_import(rs_kv* kv, int layer, const void* k_dev, const void* v_de
  *   rs_kv_pool_destroy  frees the host handle; RS_ESTATE while caches allocated from the pool are alive.
  *   rs_kv_pool_pages / rs_kv_pool_free_pages   total and currently free pages (-1 for a null pool).
  *   rs_kv_alloc_paged   an empty cache of n_layers layers on `pool` (free it with rs_kv_free before the pool).
- * The host bookkeeping is not thread-safe: one thread at a time per pool. */
+ * The host bookkeeping is not thread-safe: one thread at a time per pool.
+ * Stream ordering: pages change hands on the host, at the moment of the call, with no regard to GPU work still queued.
+ * A page that rs_kv_truncate, rs_kv_reset, rs_kv_free or a shrinking rs_kv_import gives back may be handed to another
+ * cache of the pool by the very next call.  So either run every cache of a pool on ONE stream (then the stream's order
+ * protects the page: whatever still reads it was enqueued before whatever overwrites it), or make the stream of the next
+ * taker wait (event / synchronize) for the work that last touched the cache before calling one of those four. */
 typedef struct rs_kv_pool rs_kv_pool;
 size_t rs_kv_page_bytes(const rs_ctx* ctx);
 rs_status rs_kv_pool_create(rs_ctx* ctx, void* dev_mem, size_t bytes, rs_kv_pool** out);

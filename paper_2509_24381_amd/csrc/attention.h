@@ -90,7 +90,7 @@ constexpr int ATT_KEYS = 64;   // keys per tile
 struct AttnItem {
     int req;
     int kvh;
-    int qblock;  // block of stacked query rows (128, or 256 for the wide kernel)
+    int qblock;  // block of 128 stacked query rows
     int nkb;     // number of 64-key tiles this block must visit (tiles [0, nkb), or [kb0, nkb) for a part of a split block)
     int kb0;     // first tile of this part (0 unless the block's key range is split)
     int slot;    // -1: the workgroup finishes the block and writes the output; >= 0: it leaves an unnormalised partial
@@ -112,216 +112,15 @@ struct AttnPartial {
     static constexpr size_t SLOT_FLOATS = (size_t)ATT_ROWS * (D + 2);
 };
 
-// The software-pipelined kernels keep a query's reference maximum until a tile's maximum exceeds it by more than this
+// The kernel keeps a query's reference maximum until a tile's maximum exceeds it by more than this
 // many powers of two (in the exponent's units, i.e. after the 1/sqrt(d) log2 e scaling): probabilities then reach at most
 // 2^8 instead of 1, which fp32 sums and bf16's relative rounding do not mind, and the final division by the row sum
 // cancels the reference.  Rescaling the accumulated output is thereby confined to a request's first tiles; with an
 // exact running maximum some query of a wavefront grows its maximum in almost every tile.
 constexpr float ATT_RESCALE_LOG2 = 8.0f;
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __restrict__ reqs,
-                                                              const AttnItem* __restrict__ items,
-                                                              const bf16* __restrict__ qkv, int ld_qkv,
-                                                              bf16* __restrict__ out, int ld_out,
-                                                              int g, float scale_log2e) {
-    constexpr int KSTEPS = D / 16;          // k-steps of the S^T product
-    constexpr int DT = D / 32;              // 32-row tiles of O^T
-    constexpr int K_ROW_BYTES = D * 2;
-    constexpr int K_CPR = K_ROW_BYTES / 16; // 16-byte chunks per K row: 16 (d=128) or 8 (d=64)
-    constexpr int TILE_BYTES = ATT_KEYS * D * 2;
-    constexpr int LOADS = TILE_BYTES / (256 * 16);  // 16-byte loads per thread per tile: 4 or 2
-    extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile | V^T tile]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, l32 = lane & 31;
-
-    const AttnItem item = items[blockIdx.x];
-    const ReqDesc rq = reqs[item.req];
-    const int rows_total = rq.T * g;
-    const int row = item.qblock * ATT_ROWS + wave * 32 + l32;
-    const int row_c = min(row, rows_total - 1);
-    const int tok = row_c / g;
-    const int head = item.kvh * g + (row_c - tok * g);
-    const int qpos = rq.P + tok;
-    // wave-uniform visibility bounds
-    const int wrow_lo = min(item.qblock * ATT_ROWS + wave * 32, rows_total - 1);
-    const int wrow_hi = min(item.qblock * ATT_ROWS + wave * 32 + 31, rows_total - 1);
-    const int wpos_lo = rq.P + wrow_lo / g;
-    const int wpos_hi = rq.P + wrow_hi / g;
-
-    // ---- Q fragments: 8 consecutive d values per lane per k-step
-    bf16x8 qf[KSTEPS];
-    {
-        const bf16* qp = qkv + (size_t)(rq.row0 + tok) * ld_qkv + head * D + half * 8;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
-    }
-
-    // ---- tile loader: both tiles are contiguous TILE_BYTES runs in the cache
-    uint32_t k_src_off[LOADS], v_src_off[LOADS];
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int q = i * 256 + tid;  // destination 16-byte slot in LDS
-        {
-            const int r = q / K_CPR, p = q % K_CPR;
-            const int c = (K_CPR == 16) ? (p ^ (r & 15)) : (p ^ ((r >> 1) & 7));
-            k_src_off[i] = (uint32_t)(r * K_ROW_BYTES + c * 16);
-        }
-        {
-            const int r = q >> 3, p = q & 7;
-            const int c = p ^ ((r >> 1) & 7);
-            v_src_off[i] = (uint32_t)(r * 128 + c * 16);
-        }
-    }
-    uint4 rk[LOADS], rv[LOADS];
-    const KVHeadTiles tiles = kv_head_tiles<D>(rq, item.kvh);
-    auto load_tile = [&](int kb) {
-        const int idx = tiles.index_of(kb);
-        const char* ksrc = tiles.k_tile(idx);
-        const char* vsrc = tiles.v_tile(idx);
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) rk[i] = ld_global_16(ksrc + k_src_off[i]);
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) rv[i] = ld_global_16(vsrc + v_src_off[i]);
-    };
-    auto park_tile = [&](int buf) {
-        char* ks = smem + buf * (2 * TILE_BYTES);
-        char* vs = ks + TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) *reinterpret_cast<uint4*>(ks + (i * 256 + tid) * 16) = rk[i];
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) *reinterpret_cast<uint4*>(vs + (i * 256 + tid) * 16) = rv[i];
-    };
-
-    // ---- fragment read geometry
-    // S^T product: MFMA row rho = l32 reads key pi(rho) = rho with bits 2 and 3 swapped
-    const int pi = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-    uint32_t k_row_off[2], k_swz[2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        const int r = mi * 32 + pi;
-        k_row_off[mi] = (uint32_t)(r * K_ROW_BYTES);
-        k_swz[mi] = (K_CPR == 16) ? (uint32_t)(r & 15) : (uint32_t)((r >> 1) & 7);
-    }
-    const uint32_t v_swz = (uint32_t)((lane >> 1) & 7);
-
-    f32x16 acc_o[DT];
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.0f;
-    float m_run = -INFINITY;  // running max of the raw scores of this lane's query (shared by both half-waves)
-    float l_run = 0.0f;       // running sum over THIS half-wave's keys
-
-    const int nkb = item.nkb;
-    load_tile(0);
-    park_tile(0);
-    __syncthreads();
-
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int buf = kb & 1;
-        const bool more = (kb + 1) < nkb;
-        if (more) load_tile(kb + 1);
-        const int key0 = kb * ATT_KEYS;
-        if (key0 <= wpos_hi) {  // some query of this wavefront sees some key of the tile
-            const char* ks = smem + buf * (2 * TILE_BYTES);
-            const char* vs = ks + TILE_BYTES;
-            f32x16 s[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[mi][r] = 0.0f;
-            // the two 32-key halves are independent accumulation chains: alternate them so that no MFMA waits for
-            // the result of the one issued just before it
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk)
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
-                    bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_row_off[mi] + c);
-                    s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mi], 0, 0, 0);
-                }
-            // register r of s[mi] holds key  key0 + mi*32 + 16*(r>>3) + 8*half + (r&7)
-            if (key0 + ATT_KEYS - 1 > wpos_lo) {  // tile straddles the causal boundary of some query here
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + mi * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
-                        s[mi][r] = (key <= qpos) ? s[mi][r] : -INFINITY;
-                    }
-            }
-            float mloc = s[0][0];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[mi][r]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, WAVE));
-            const float m_new = fmaxf(m_run, mloc);          // finite: key 0 is visible to every query
-            // the accumulated output is rescaled only when some query of this wavefront saw its running max grow
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
-                l_run *= alpha;
-#pragma unroll
-                for (int t = 0; t < DT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
-            }
-            const float mb = m_new * scale_log2e;
-            m_run = m_new;
-            float psum = 0.0f;
-            bf16x8 pf[4];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // raw v_exp_f32: arguments are <= 0, results below the normal range may flush to zero
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mi][r], scale_log2e, -mb));
-                    psum += p;
-                    pf[mi * 2 + (r >> 3)][r & 7] = f32_to_bf16(p);
-                }
-            l_run += psum;
-            // the DT output tiles are independent chains: walk the keys in the outer loop
-#pragma unroll
-            for (int ksx = 0; ksx < 4; ++ksx) {
-                const uint32_t c = ((uint32_t)(ksx * 2 + half) ^ v_swz) * 16u;
-#pragma unroll
-                for (int t = 0; t < DT; ++t) {
-                    const uint32_t vrow = (uint32_t)(t * 32 + l32) * 128u;
-                    bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + vrow + c);
-                    acc_o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ksx], acc_o[t], 0, 0, 0);
-                }
-            }
-        }
-        if (more) park_tile(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- normalise and store.  acc_o[t][r]: d = t*32 + 8*(r>>2) + 4*half + (r&3), query = this lane's row.
-    //      The output is the output projection's token operand: fragment-major of width ld_out (blocks of 32 tokens x 16
-    //      features, the two 8-feature halves 512 bytes apart, tokens 16 bytes apart).
-    const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
-    if (row < rows_total) {
-        const float inv = 1.0f / l_tot;
-        const uint32_t m = (uint32_t)(rq.row0 + tok);
-        char* op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u + half * 8;
-        const int ks0 = (head * D) >> 4;
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                bf16x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc_o[t][4 * q + e] * inv);
-                *reinterpret_cast<bf16x4*>(op + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o;
-            }
-    }
-}
-
-
 // ------------------------------------------------------------------------------------------------------------------
-// Software-pipelined variant of the same computation.  Per key tile a wavefront has two kinds of work: 32 MFMAs (the two
+// The kernel is software-pipelined across key tiles.  Per key tile a wavefront has two kinds of work: 32 MFMAs (the two
 // products) and the online softmax on the vector ALU (an exponential per score at a quarter of the ALU rate, plus the
 // scaling, the running maximum, the row sum and the bf16 conversion), about equally long; run one after the other, the
 // matrix pipe idles half of the time.  Here the score product of tile kb+1 is issued between the exponentials of tile
@@ -330,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const ReqDesc* __r
 // K(kb+2) and V(kb+1) travel global -> LDS by DMA (buffer_load ... lds: no staging registers) into the buffers that
 // iteration kb-1 finished with.  The four buffers are separate LDS objects so that the compiler can tell that the
 // fragment reads of an iteration do not touch the buffers being filled; it waits for the DMA at the barrier that ends
-// the iteration.
+// the iteration.  Two workgroups share a compute unit (256 registers per lane each).
 template <int D, bool MAY_PAGE>
 __global__ __launch_bounds__(256, 2) void attn_prefill_pipelined_kernel(const ReqDesc* __restrict__ reqs,
                                                                         const AttnItem* __restrict__ items,
@@ -704,389 +503,5 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const ReqDesc* __restri
         // chunk c = 8t + 2q + half holds features 32t + 8q + 4half .. +3: the same place the unsplit kernel writes
         const int t = c >> 3, q = (c >> 1) & 3, hf = c & 1;
         *reinterpret_cast<bf16x4*>(op + hf * 8 + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o4;
-    }
-}
-
-constexpr int ATT_WIDE_ROWS = 256;
-
-// v_mfma_f32_32x32x16_bf16 with its accumulator in ordinary vector registers.  In a kernel that may use more than 256
-// registers the compiler puts every MFMA accumulator into accumulation registers, which the vector ALU cannot read; the
-// score tiles are consumed by the vector ALU, so their MFMAs are written out here.  The compiler does not know these are
-// MFMAs and inserts no wait states around them: callers keep two dependent ones at least two other MFMAs apart and read
-// the result with the vector ALU no sooner than a whole further product (dozens of MFMAs) later.
-RS_DEVICE void mfma_scores_first(f32x16& d, const bf16x8& a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
-}
-RS_DEVICE void mfma_scores_acc(f32x16& d, const bf16x8& a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
-}
-
-// Development builds (RS_ATTN_TIMING) take shader-clock stamps at the phase boundaries of every iteration and leave the
-// per-workgroup sums in a buffer; product builds compile the stamps away.
-#ifdef RS_ATTN_TIMING
-#define RS_ATTN_STAMP(i)                                                                  \
-    do {                                                                                  \
-        unsigned long long t_now;                                                         \
-        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t_now));                \
-        dbg_acc[i] += t_now - dbg_last;                                                   \
-        dbg_last = t_now;                                                                 \
-    } while (0)
-#define RS_ATTN_TIMING_PARAM , unsigned long long* __restrict__ dbg
-#else
-#define RS_ATTN_STAMP(i)
-#define RS_ATTN_TIMING_PARAM
-#endif
-
-template <int D>
-__global__ __launch_bounds__(256, 1) void attn_prefill_wide_kernel(const ReqDesc* __restrict__ reqs,
-                                                                   const AttnItem* __restrict__ items,
-                                                                   const bf16* __restrict__ qkv, int ld_qkv,
-                                                                   bf16* __restrict__ out, int ld_out,
-                                                                   int g, float scale_log2e RS_ATTN_TIMING_PARAM) {
-#ifdef RS_ATTN_TIMING
-    unsigned long long dbg_acc[6] = {0, 0, 0, 0, 0, 0}, dbg_last;
-    asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_last));
-#endif
-    constexpr int NQ = 2;
-    constexpr int KSTEPS = D / 16;
-    constexpr int DT = D / 32;
-    constexpr int K_ROW_BYTES = D * 2;
-    constexpr int K_CPR = K_ROW_BYTES / 16;
-    constexpr int TILE_BYTES = ATT_KEYS * D * 2;
-    constexpr int LOADS = TILE_BYTES / (256 * 16);
-    typedef __attribute__((address_space(3))) void* lds_ptr;
-    __shared__ __attribute__((aligned(16))) char k_buf0[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) char k_buf1[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) char v_buf0[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) char v_buf1[TILE_BYTES];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = lane >> 5, l32 = lane & 31;
-
-    const AttnItem item = items[blockIdx.x];
-    const ReqDesc rq = reqs[item.req];
-    const int rows_total = rq.T * g;
-    int row[NQ], tok[NQ], head[NQ], qpos[NQ];
-#pragma unroll
-    for (int nj = 0; nj < NQ; ++nj) {
-        row[nj] = item.qblock * ATT_WIDE_ROWS + wave * 64 + nj * 32 + l32;
-        const int row_c = min(row[nj], rows_total - 1);
-        tok[nj] = row_c / g;
-        head[nj] = item.kvh * g + (row_c - tok[nj] * g);
-        qpos[nj] = rq.P + tok[nj];
-    }
-    const int wrow_lo = min(item.qblock * ATT_WIDE_ROWS + wave * 64, rows_total - 1);
-    const int wpos_lo = rq.P + wrow_lo / g;  // every query of this wavefront sees all keys <= wpos_lo
-
-    bf16x8 qf[NQ][KSTEPS];
-#pragma unroll
-    for (int nj = 0; nj < NQ; ++nj) {
-        const bf16* qp = qkv + (size_t)(rq.row0 + tok[nj]) * ld_qkv + head[nj] * D + half * 8;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) qf[nj][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
-    }
-
-    // ---- tile loader (as in the kernel above)
-    const int nkb = item.nkb;
-    uint32_t k_src_off[4], v_src_off[4];  // (fixed bound: LOADS <= 4)
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int q = i * 256 + tid;
-        {
-            const int r = q / K_CPR, p = q % K_CPR;
-            const int c = (K_CPR == 16) ? (p ^ (r & 15)) : (p ^ ((r >> 1) & 7));
-            k_src_off[i] = (uint32_t)(r * K_ROW_BYTES + c * 16);
-        }
-        {
-            const int r = q >> 3, p = q & 7;
-            const int c = p ^ ((r >> 1) & 7);
-            v_src_off[i] = (uint32_t)(r * 128 + c * 16);
-        }
-    }
-    const KVHeadTiles tiles = kv_head_tiles<D>(rq, item.kvh);
-    auto fetch_k = [&](char* buf, int kb) {
-        if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rk =
-                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.k_tile(tiles.index_of(kb)), 0, TILE_BYTES, 0x00020000);
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, k_src_off[i],
-                                                         0, 0, 0);
-        }
-    };
-    auto fetch_v = [&](char* buf, int kb) {
-        if (kb < nkb) {
-            const __amdgpu_buffer_rsrc_t rv =
-                __builtin_amdgcn_make_buffer_rsrc((void*)tiles.v_tile(tiles.index_of(kb)), 0, TILE_BYTES, 0x00020000);
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr)(uintptr_t)(uint32_t)(uintptr_t)(buf + (i * 256 + wave * 64) * 16), 16, v_src_off[i],
-                                                         0, 0, 0);
-        }
-    };
-
-    const int pi = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-    uint32_t k_row_off[2], k_swz[2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        const int r = mi * 32 + pi;
-        k_row_off[mi] = (uint32_t)(r * K_ROW_BYTES);
-        k_swz[mi] = (K_CPR == 16) ? (uint32_t)(r & 15) : (uint32_t)((r >> 1) & 7);
-    }
-    const uint32_t v_swz = (uint32_t)((lane >> 1) & 7);
-
-    f32x16 acc_o[DT][NQ];
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[t][nj][r] = 0.0f;
-    float m_run[NQ], l_run[NQ], alpha[NQ];
-#pragma unroll
-    for (int nj = 0; nj < NQ; ++nj) {
-        m_run[nj] = -INFINITY;  // running max of the raw scores of this lane's query nj (shared by both half-waves)
-        l_run[nj] = 0.0f;       // running sum over THIS half-wave's keys
-        alpha[nj] = 1.0f;       // factor the accumulated output still has to be multiplied by before the next P.V
-    }
-    bool rescale = false;  // some query of this wavefront saw its maximum grow (wave-uniform)
-
-    // raw scores of one tile: register r of s[mi][nj] holds key  key0 + mi*32 + 16*(r>>3) + 8*half + (r&7)  of query nj
-    auto mask_scores = [&](f32x16 (&s)[2][NQ], int key0) {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int nj = 0; nj < NQ; ++nj)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + mi * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
-                    s[mi][nj][r] = (key <= qpos[nj]) ? s[mi][nj][r] : -INFINITY;
-                }
-    };
-    // closes the running maximum of a tile from the lane-local maxima
-    auto close_max = [&](float (&mloc)[NQ]) {
-        bool grew = false;
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj) {
-            const float mw = fmaxf(mloc[nj], __shfl_xor(mloc[nj], 32, WAVE));
-            // finite from the first tile on: key 0 is visible to every query
-            const float m_new = ((mw - m_run[nj]) * scale_log2e > ATT_RESCALE_LOG2) ? mw : m_run[nj];
-            grew = grew || (m_new != m_run[nj]);
-            alpha[nj] = __builtin_amdgcn_exp2f((m_run[nj] - m_new) * scale_log2e);
-            m_run[nj] = m_new;
-        }
-        rescale = __builtin_amdgcn_ballot_w64(grew) != 0;
-    };
-
-    // ---- prologue: K(0), V(0), K(1) into LDS; scores and maximum of tile 0
-    fetch_k(k_buf0, 0);
-    fetch_v(v_buf0, 0);
-    fetch_k(k_buf1, 1);
-    __syncthreads();
-    const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    f32x16 svA[2][NQ], svB[2][NQ];  // raw scores of two consecutive tiles (ordinary vector registers)
-    {
-        f32x16 s0[2][NQ];
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk)
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_buf0 + k_row_off[mi] + c);
-#pragma unroll
-                for (int nj = 0; nj < NQ; ++nj)
-                    s0[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nj][kk], kk == 0 ? zero16 : s0[mi][nj], 0, 0, 0);
-            }
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int nj = 0; nj < NQ; ++nj) svA[mi][nj] = s0[mi][nj];
-        if (ATT_KEYS - 1 > wpos_lo) mask_scores(svA, 0);
-        float mloc[NQ];
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj) {
-            mloc[nj] = svA[0][nj][0];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) mloc[nj] = fmaxf(fmaxf(svA[mi][nj][r], svA[mi][nj][r + 1]), mloc[nj]);
-        }
-        close_max(mloc);
-    }
-    __syncthreads();  // every wavefront is done with K(0): iteration 0 may overwrite it
-
-    // one iteration: scur = raw scores of tile kb (masked, maximum known); snext receives those of tile kb+1.
-    // k_next holds K(kb+1), v_cur V(kb); k_fill (= K(kb)'s buffer) receives K(kb+2), v_fill (= V(kb-1)'s) V(kb+1).
-    auto iteration = [&](int kb, f32x16 (&scur)[2][NQ], f32x16 (&snext)[2][NQ], const char* k_next, char* k_fill,
-                         const char* v_cur, char* v_fill) {
-        RS_ATTN_STAMP(0);  // 0: between iterations (barrier exit, loop control)
-        fetch_k(k_fill, kb + 2);
-        fetch_v(v_fill, kb + 1);
-        float mb[NQ];
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj) mb[nj] = m_run[nj] * scale_log2e;
-        bf16x8 pf[NQ][4];  // pf[nj][q]: probabilities of keys 16q + 8*half .. +7 of the tile, query nj
-        float psum[NQ];
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj) psum[nj] = 0.0f;
-        // The tile's 32*NQ values are taken in the order the second product consumes them: value v belongs to key group
-        // q = v / (8 NQ), query nj = (v / 8) % NQ, element e = v % 8.  Each value: scale, subtract, exponential; every
-        // second one also converts the pair to bf16 and adds it to the row sum.
-        float p_even = 0.0f;
-        auto one_value = [&](int v) {
-            const int grp = v >> 3, q = grp / NQ, nj = grp % NQ, e = v & 7, mi = q >> 1, r = (q & 1) * 8 + e;
-            // raw v_exp_f32: arguments are <= ATT_RESCALE_LOG2, results below the normal range may flush to zero
-            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[mi][nj][r], scale_log2e, -mb[nj]));
-            if ((v & 1) == 0) {
-                p_even = pv;
-                asm volatile("" : "+v"(p_even));  // pins this value's work where it is written
-            } else {
-                const bf16x2 pp = {f32_to_bf16(p_even), f32_to_bf16(pv)};
-                psum[nj] += p_even + pv;  // plain adds: dot instructions do not run beside an MFMA
-                pf[nj][q][e - 1] = pp[0];
-                pf[nj][q][e] = pp[1];
-                asm volatile("" : "+v"(psum[nj]));
-            }
-        };
-        constexpr int NVAL = 32 * NQ;            // values per tile and lane
-        constexpr int NS = 2 * KSTEPS;           // score steps (one K fragment, NQ MFMAs each)
-        constexpr int V1 = NVAL * 5 / 8;         // values handled behind the score MFMAs (key groups 0, 1 and half of 2)
-        // ---- phase 1: S(kb+1) = K(kb+1) Q^T, with the first V1 values of P(kb) between its MFMAs
-        auto k_frag = [&](int step) {
-            const int kk = step >> 1, mi = step & 1;
-            const uint32_t c = ((uint32_t)(kk * 2 + half) ^ k_swz[mi]) * 16u;
-            return *reinterpret_cast<const bf16x8*>(k_next + k_row_off[mi] + c);
-        };
-        auto v_frag = [&](int step) {
-            const int q = step / DT, t = step % DT;
-            const uint32_t c = ((uint32_t)(q * 2 + half) ^ v_swz) * 16u;
-            return *reinterpret_cast<const bf16x8*>(v_cur + (uint32_t)(t * 32 + l32) * 128u + c);
-        };
-        // fragments are read from LDS two steps (2 NQ MFMAs) ahead of their use: with one wavefront per SIMD nothing else
-        // covers the read's latency
-        bf16x8 kfr[3];
-        kfr[0] = k_frag(0);
-        kfr[1] = k_frag(1);
-#pragma unroll
-        for (int step = 0; step < NS; ++step) {
-            if (step + 2 < NS) kfr[(step + 2) % 3] = k_frag(step + 2);
-            __builtin_amdgcn_sched_barrier(0);  // the read goes out first
-            const bf16x8 kf = kfr[step % 3];
-#pragma unroll
-            for (int nj = 0; nj < NQ; ++nj) {
-                if (step < 2) mfma_scores_first(snext[step & 1][nj], kf, qf[nj][step >> 1]);
-                else mfma_scores_acc(snext[step & 1][nj], kf, qf[nj][step >> 1]);
-                constexpr int SLOTS = NS * NQ;
-                const int slot = step * NQ + nj;
-#pragma unroll
-                for (int v = slot * V1 / SLOTS; v < (slot + 1) * V1 / SLOTS; ++v) one_value(v);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        RS_ATTN_STAMP(1);  // 1: loads issued + score product with its share of the exponentials
-        bf16x8 vfr[3];
-        vfr[0] = v_frag(0);
-        vfr[1] = v_frag(1);
-        // ---- the accumulated output catches up with the maximum of tile kb
-        //      (rare after a request's first tiles).  The output lives in accumulation registers, which the vector ALU
-        //      reaches only through explicit moves; written as such, the values on both sides of the branch stay in that
-        //      register class (a plain multiply here makes the compiler move all of them out and back in every iteration,
-        //      taken or not).  The last MFMA on these registers is a whole score product back; the trailing s_nop covers
-        //      the wait states between a move into an accumulation register and the MFMA that reads it.
-        if (rescale) {
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int nj = 0; nj < NQ; ++nj)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float x, y;
-                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc_o[t][nj][r]));
-                        x *= alpha[nj];
-                        asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(y) : "v"(x));
-                        acc_o[t][nj][r] = y;
-                    }
-            asm volatile("s_nop 7\n\ts_nop 7");
-        }
-        const int key1 = (kb + 1) * ATT_KEYS;
-        const bool more = kb + 1 < nkb;
-        // ---- phase 2: O += V(kb)^T P(kb), key group by key group.  Behind the MFMAs of groups 0..2: the remaining values
-        //      of P(kb) (those of group q+1 at the latest behind group q); then the mask; behind the MFMAs of group 3 the
-        //      maximum of tile kb+1.
-        RS_ATTN_STAMP(2);  // 2: output rescale (when taken)
-        constexpr int NV = 4 * DT;               // P.V steps (one V fragment, NQ MFMAs each)
-        constexpr int SLOTS2 = 3 * DT * NQ;      // MFMAs of key groups 0..2
-        constexpr int V2 = NVAL - V1;
-        constexpr int MSLOTS = DT * NQ;          // MFMAs of key group 3
-        float mloc[NQ];
-#pragma unroll
-        for (int step = 0; step < NV; ++step) {
-            if (step + 2 < NV) vfr[(step + 2) % 3] = v_frag(step + 2);
-            const bf16x8 vf = vfr[step % 3];
-            if (step == 3 * DT) {
-                if (more && key1 + ATT_KEYS - 1 > wpos_lo) mask_scores(snext, key1);  // some query here does not see the whole next tile
-#pragma unroll
-                for (int nj = 0; nj < NQ; ++nj) mloc[nj] = snext[0][nj][0];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int nj = 0; nj < NQ; ++nj) {
-                acc_o[step % DT][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nj][step / DT], acc_o[step % DT][nj], 0, 0, 0);
-                const int slot = step * NQ + nj;
-                if (slot < SLOTS2) {
-#pragma unroll
-                    for (int v = V1 + slot * V2 / SLOTS2; v < V1 + (slot + 1) * V2 / SLOTS2; ++v) one_value(v);
-                } else {
-                    // 16 NQ pair-maxima of tile kb+1 over MSLOTS slots
-                    const int ms = slot - SLOTS2;
-#pragma unroll
-                    for (int i = ms * (16 * NQ) / MSLOTS; i < (ms + 1) * (16 * NQ) / MSLOTS; ++i) {
-                        const int qn = i / 16, mi = (i >> 3) & 1, r = (i & 7) * 2;
-                        mloc[qn] = fmaxf(fmaxf(snext[mi][qn][r], snext[mi][qn][r + 1]), mloc[qn]);
-                        asm volatile("" : "+v"(mloc[qn]));
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        RS_ATTN_STAMP(3);  // 3: P.V product with the rest of the exponentials and the next maximum
-#pragma unroll
-        for (int nj = 0; nj < NQ; ++nj) l_run[nj] = l_run[nj] * alpha[nj] + psum[nj];
-        if (more) close_max(mloc);
-        RS_ATTN_STAMP(4);  // 4: closing the maximum
-        __syncthreads();
-        RS_ATTN_STAMP(5);  // 5: wait for the DMA and the barrier
-    };
-
-    int kb = 0;
-    for (; kb + 1 < nkb; kb += 2) {
-        iteration(kb, svA, svB, k_buf1, k_buf0, v_buf0, v_buf1);
-        iteration(kb + 1, svB, svA, k_buf0, k_buf1, v_buf1, v_buf0);
-    }
-    if (kb < nkb) iteration(kb, svA, svB, k_buf1, k_buf0, v_buf0, v_buf1);
-#ifdef RS_ATTN_TIMING
-    if (tid == 0)
-        for (int i = 0; i < 6; ++i) dbg[blockIdx.x * 8 + i] = dbg_acc[i];
-#endif
-
-#pragma unroll
-    for (int nj = 0; nj < NQ; ++nj) {
-        const float l_tot = l_run[nj] + __shfl_xor(l_run[nj], 32, WAVE);
-        if (row[nj] < rows_total) {
-            const float inv = 1.0f / l_tot;
-            const uint32_t m = (uint32_t)(rq.row0 + tok[nj]);
-            char* op = reinterpret_cast<char*>(out) + (size_t)(m >> 5) * (size_t)(ld_out >> 4) * 1024 + (m & 31u) * 16u + half * 8;
-            const int ks0 = (head[nj] * D) >> 4;
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(acc_o[t][nj][4 * q + e] * inv);
-                    *reinterpret_cast<bf16x4*>(op + (size_t)(((ks0 + 2 * t + (q >> 1)) * 2 + (q & 1)) * 512)) = o;
-                }
-        }
     }
 }

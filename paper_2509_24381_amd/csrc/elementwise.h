@@ -10,7 +10,7 @@
 // halves 512 bytes apart, tokens 16 bytes apart (rows of the last block past `rows` are left untouched: they are never
 // used).  One workgroup handles 8 tokens: 32 threads read 512 contiguous bytes of one token per step, and the 8 tokens'
 // 16-byte chunks of one (k-step, half) land in 128 contiguous bytes (one cache line).
-// Workgroups past the row blocks copy the call's descriptors (requests, attention work items, cache blocks, row
+// The first workgroups of the grid copy the call's descriptors (requests, attention work items, cache blocks, row
 // positions) from the pinned host buffer the library filled, which the device reads in place, into the workspace: the
 // later kernels of the call then find them in device memory, and no copy command sits between two calls (a runtime copy
 // of a few tens of KB costs a blit kernel of 13 us plus the gaps around it).
@@ -18,14 +18,16 @@ __global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16*
                                                                      float* __restrict__ inv_rms, int rows, int H, float eps,
                                                                      const uint4* __restrict__ desc_src,
                                                                      uint4* __restrict__ desc_dst, int desc_chunks) {
-    const int row_blocks = (rows + 7) >> 3;
-    if ((int)blockIdx.x >= row_blocks) {
-        const int i = ((int)blockIdx.x - row_blocks) * 256 + (int)threadIdx.x;
+    // (the copying workgroups come first in the grid: their reads cross the host link, several microseconds each, and
+    // should be under way while the row blocks stream; launched last they were the tail of the kernel)
+    const int desc_blocks = (desc_chunks + 255) >> 8;
+    if ((int)blockIdx.x < desc_blocks) {
+        const int i = (int)blockIdx.x * 256 + (int)threadIdx.x;
         if (i < desc_chunks) desc_dst[i] = desc_src[i];
         return;
     }
     const int r = threadIdx.x >> 5, c = threadIdx.x & 31;
-    const int m = blockIdx.x * 8 + r;
+    const int m = ((int)blockIdx.x - desc_blocks) * 8 + r;
     const int mc = min(m, rows - 1);  // threads of rows past the end follow along (their shuffles are needed) and store nothing
     const char* src = reinterpret_cast<const char*>(x + (size_t)mc * H) + c * 16;
     char* out = reinterpret_cast<char*>(dst) + ((size_t)(m >> 5) * (H >> 4) * 2 + c) * 512 + (m & 31) * 16;
@@ -51,18 +53,6 @@ __global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16*
 #pragma unroll
     for (int off = 16; off > 0; off >>= 1) ss += __shfl_xor(ss, off, WAVE);
     if (c == 0 && m < rows) inv_rms[m] = rsqrtf(ss / (float)H + eps);
-}
-
-// inv_rms[m] = rsqrt(sum_u rowss[m][u] / H + eps): closes the per-row sums of squares left by the EPI_RESIDUAL epilogue.
-__global__ __launch_bounds__(256) void rowss_finalize_kernel(const float* __restrict__ rowss, int units, int M, int H,
-                                                             float eps, float* __restrict__ inv_rms) {
-    const int lane = threadIdx.x & 63;
-    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (m >= M) return;
-    float ss = 0.0f;
-    for (int u = lane; u < units; u += WAVE) ss += rowss[(size_t)m * units + u];
-    ss = wave_sum(ss);
-    if (lane == 0) inv_rms[m] = rsqrtf(ss / (float)H + eps);
 }
 
 // ---------------------------------------------------------------- first-token head: final RMSNorm + vocabulary projection

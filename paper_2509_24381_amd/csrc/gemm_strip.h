@@ -46,7 +46,13 @@ struct GemmArgs {
     bf16* out;          // [M, ldo], row-major or (out_frag) fragment-major of width ldo
     const bf16* bias;   // [N] in the original feature order, or null
     const bf16* resid;  // [M, ldr], row-major or (resid_frag) fragment-major of width ldr
-    float* rowss;       // EPI_RESIDUAL: [M][N/32] sum of squares of each stored run of 32 features, or null
+    float* rowss;       // EPI_RESIDUAL (output, or null): [parts][M], one sum of squares per row and workgroup column - a strip
+                        // (times the wavefronts that split its units) - over the features of the stored row that the column
+                        // owns; parts = rowss_parts(...) of this launch.  EPI_SWIGLU (input, or null): the same array as the
+                        // residual GEMM in front left it; the row factor is then rsqrt(sum of the parts / K + rms_eps)
+                        // instead of row_scale[m]
+    int rowss_parts;    // EPI_SWIGLU: number of parts in rowss
+    float rms_eps;      // EPI_SWIGLU with rowss
     float* partial;     // [splits, M, N]
     const float* row_scale;  // [M] 1/rms of the row (EPI_QKV_ROPE, EPI_SWIGLU)
     const int* row_pos;      // [M][3] rotary position of the row on the (temporal, height, width) axes (EPI_QKV_ROPE)
@@ -60,9 +66,6 @@ struct GemmArgs {
     int tiles_m;             // ceil(M / 256)
     int strips;              // strips per 256-row block; grid.x = tiles_m * strips
     int steps_per_split;     // K/64 steps handled by one blockIdx.y
-#ifdef RS_GEMM_TIMING
-    unsigned long long* dbg;  // development only: [grid.x][2] shader-clock stamps at workgroup start and end
-#endif
 };
 
 constexpr int GS_BM = 256;
@@ -129,7 +132,10 @@ RS_DEVICE u32x4 pair_runs(bf16x4 even_run, bf16x4 odd_run) {
 // back).  The empty asm statement at the top of each unit's iteration pins that unit's tile in accumulation registers up to
 // there, so the copies are made 16 registers at a time and nothing spills.
 template <int EPI, int NT, int USTRIDE = 1>
-RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base, int unit0, int half, int l32, int split) {
+RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base, int unit0, int half, int l32, int split,
+                             float (&row_val)[2]) {
+    // row_val[j], one value per lane and token block j: EPI_SWIGLU reads the row's factor 1/rms there; EPI_RESIDUAL adds
+    // the sum of squares of what it stores of the row (this lane's 16 of each unit's 32 features)
     constexpr int RSRC_FLAGS = 0x00020000;
     const int m_pad = (a.M + 31) & ~31;  // fragment-major buffers hold whole blocks of 32 tokens
 #pragma unroll
@@ -139,8 +145,7 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
             // the output is the next GEMM's token operand: always fragment-major.  Unit u holds features 16u..16u+15 = one
             // k-step of it, q selects the 8-feature half, so the 64 lanes of a store cover 512 contiguous bytes
             const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, m_pad * a.ldo * 2, RSRC_FLAGS);
-            const __amdgpu_buffer_rsrc_t r_sc = __builtin_amdgcn_make_buffer_rsrc((void*)a.row_scale, 0, a.M * 4, RSRC_FLAGS);
-            const float sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r_sc, m * 4, 0, 0));
+            const float sc = row_val[j];
             const uint32_t oblk = (uint32_t)(m >> 5) * (uint32_t)(a.ldo >> 4) * 1024u + (uint32_t)l32 * 16u + (uint32_t)half * 512u;
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
@@ -245,8 +250,6 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                 __builtin_amdgcn_make_buffer_rsrc((void*)a.out, 0, (a.out_frag ? m_pad : a.M) * a.ldo * 2, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t r_res =
                 __builtin_amdgcn_make_buffer_rsrc((void*)a.resid, 0, (a.resid_frag ? m_pad : a.M) * a.ldr * 2, RSRC_FLAGS);
-            const __amdgpu_buffer_rsrc_t r_ss =
-                __builtin_amdgcn_make_buffer_rsrc((void*)a.rowss, 0, a.rowss != nullptr ? a.M * (a.N >> 5) * 4 : 0, RSRC_FLAGS);
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 asm volatile("" : "+a"(acc[i][j]));
@@ -270,11 +273,8 @@ RS_DEVICE void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[NT][2], int m_base
                     const uint32_t ooff = a.out_frag ? frag_offset_bytes(m, n, a.ldo) : ((uint32_t)m * (uint32_t)a.ldo + n) * 2u;
                     __builtin_amdgcn_raw_buffer_store_b128(pair_runs(o[2 * pr], o[2 * pr + 1]), r_out, ooff, 0, 0);
                 }
-                // the two half-waves hold the two halves of this token's 32 features of the unit; half 0 stores the sum
-                // (an empty resource when no sums are wanted; half 1 and rows past M aim outside it)
-                ss += __shfl_xor(ss, 32, WAVE);
-                const uint32_t soff = half ? 0x80000000u : ((uint32_t)m * (uint32_t)(a.N >> 5) + (uint32_t)(unit0 + i * USTRIDE)) * 4u;
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, ss), r_ss, soff, 0, 0);
+                row_val[j] += ss;
+                asm volatile("" : "+v"(row_val[j]));   // (one unit at a time: keeps the residual loads of later units from being hoisted)
             }
         }
     }
@@ -318,10 +318,6 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
     const int half = lane >> 5;
     const int l32 = lane & 31;
 
-#ifdef RS_GEMM_TIMING
-    unsigned long long dbg_t0;
-    asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_t0));
-#endif
     // ---- which strip: workgroup ids are dispatched round-robin over the 8 XCDs; re-map them so that each XCD owns a
     //      contiguous range of strips (all token blocks of a weight range run on one XCD, close in time: the weight stream
     //      crosses the L2 boundary once)
@@ -422,6 +418,10 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
 
     const bool wave_has_rows = m0 + tw * 64 < a.M;   // (uniform per wavefront)
 
+    // ---- one value per lane and token block j (token m0 + tw*64 + j*32 + l32): the RMSNorm factor of the row for the
+    //      SwiGLU epilogue, the running sum of squares of the stored row for the residual epilogue (see gemm_epilogue)
+    float row_val[2] = {0.0f, 0.0f};
+
     // ---- weight fragment addresses inside a slot: row l32 of unit i at i*4096 + l32*128, chunk (2 kk + half) swizzled
     uint32_t aw[4];
 #pragma unroll
@@ -443,7 +443,45 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
         x_advance();
     });
     prologue_w();
+    if constexpr (EPI == EPI_SWIGLU) {
+        // The row factors, behind the pipeline's first loads (and waited for with them).  With rowss the residual GEMM in
+        // front left rowss_parts partial sums of squares per row, [part][M]: half 0 of the wavefront adds the even parts,
+        // half 1 the odd ones, in ascending order (one fixed order: the result does not depend on anything else).
+        int mj[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) mj[j] = min(m0 + tw * 64 + j * 32 + l32, a.M - 1);   // (rows past M: any valid row, nothing is stored)
+        if (a.rowss != nullptr) {
+            constexpr int B = 16;   // loads in flight per row: a pass covers 2 B parts (32 strips at 2048 rows: one pass)
+            for (int p0 = half; p0 < a.rowss_parts; p0 += 2 * B) {
+                float v[2][B];
+#pragma unroll
+                for (int u = 0; u < B; ++u)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int p = p0 + 2 * u;
+                        v[j][u] = a.rowss[(size_t)min(p, a.rowss_parts - 1) * a.M + mj[j]];
+                        if (p >= a.rowss_parts) v[j][u] = 0.0f;
+                    }
+#pragma unroll
+                for (int u = 0; u < B; ++u)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) row_val[j] += v[j][u];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) row_val[j] = a.row_scale[mj[j]];
+        }
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (EPI == EPI_SWIGLU) {
+        if (a.rowss != nullptr) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float ss = row_val[j] + __shfl_xor(row_val[j], 32, WAVE);
+                row_val[j] = rsqrtf(ss / (float)a.K + a.rms_eps);
+            }
+        }
+    }
 
     auto run_tile = [&](auto ntc, const int unit0) {
         constexpr int NT = decltype(ntc)::value;   // units of the tile (= weight DMA instructions per step and wavefront)
@@ -660,7 +698,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
         } else {
             tie_wait_lgkm0<NTW>(wa);
         }
-        gemm_epilogue<EPI, NTW, WU>(a, acc, m0 + tw * 64, unit0 + uw, half, l32, split);
+        gemm_epilogue<EPI, NTW, WU>(a, acc, m0 + tw * 64, unit0 + uw, half, l32, split, row_val);
     };
 
     for (int t = 0; t < ntiles; ++t) {
@@ -684,14 +722,18 @@ __global__ __launch_bounds__(256, OCC) void gemm_strip_kernel(GemmArgs a) {
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stream's last (empty) loads still target this workgroup's LDS
-#ifdef RS_GEMM_TIMING
-    if (tid == 0 && blockIdx.y == 0) {
-        unsigned long long dbg_t1;
-        asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(dbg_t1));
-        a.dbg[blockIdx.x * 2] = dbg_t0;
-        a.dbg[blockIdx.x * 2 + 1] = dbg_t1;
+    if constexpr (EPI == EPI_RESIDUAL) {
+        // what this workgroup column stored of each row, squared and summed: the two half-waves hold the two halves of a
+        // token's features, half 0 stores (rows past M, and a launch that wants no sums, store nothing)
+        if (a.rowss != nullptr && wave_has_rows) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float ss = row_val[j] + __shfl_xor(row_val[j], 32, WAVE);
+                const int m = m0 + tw * 64 + j * 32 + l32;
+                if (half == 0 && m < a.M) a.rowss[(size_t)(strip * WU + uw) * a.M + m] = ss;
+            }
+        }
     }
-#endif
 }
 
 // Sums split-K partials, adds the residual and rounds once:  out[m,n] = bf16(resid[m,n] + sum_s partial[s][m][n]).

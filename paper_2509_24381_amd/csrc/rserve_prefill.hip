@@ -79,13 +79,12 @@ struct rs_ctx {
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
     int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
     int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
-    int attn_variant = 1;     // RS_ATTN environment variable: 2 the wide software-pipelined attention kernel (256 rows per
-                              // workgroup), 1 the 128-row software-pipelined one, 0 the plain one
     int gemm_pairs = 1;       // RS_PAIRS environment variable: 0 never lets two wavefronts of a GEMM workgroup split a pair of units
     int gemm_narrow = 1;      // RS_NARROW environment variable: 0 never uses the narrow GEMM geometry; otherwise launches of at most
     int narrow_max_tiles_m = 1;  // narrow_max_tiles_m (RS_NARROW_TM) token blocks whose strips would hold at most 2 units use it
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
+    int lm_rows = 0;          // rows per launch of the first-token head (0: its LDS size not yet set, see rs_lm_head)
     // measurement hook: HIP events around every launch of one step of the layer
     int prof_step = -1;
     int prof_count = 0;
@@ -269,8 +268,10 @@ size_t fp8_expansion_bytes(const rs_ctx* c, long n_tokens) {
     return (size_t)2 * align_up((size_t)n_tokens, 64) * c->kv_dim * 2;
 }
 
+// *columns_out (optional) receives the number of workgroup columns of the launch: strips times the wavefronts that split a
+// strip's units, i.e. the number of parts the residual epilogue leaves in GemmArgs::rowss.
 template <int EPI>
-rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
+rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st, int* columns_out = nullptr) {
     a.tiles_m = (a.M + GS_BM - 1) / GS_BM;
     const int units = a.N / 32;
     const int steps = a.K / GS_BK;
@@ -285,6 +286,7 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
         if (strips == units / 2) {
             a.tiles_m = tiles_m;
             a.strips = strips;
+            if (columns_out) *columns_out = 2 * strips;
             hipLaunchKernelGGL((gemm_strip_kernel<EPI, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>), dim3(tiles_m * strips, splits),
                                dim3(256), GS_NARROW_LDS_BYTES, st, a);
             RS_HIP(hipGetLastError());
@@ -292,6 +294,7 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
         }
     }
     a.strips = strips_for(c, a.tiles_m, splits, units);
+    if (columns_out) *columns_out = a.strips;
     dim3 grid(a.tiles_m * a.strips, splits);
     // (the QKV projection, which is never split along K, also takes the narrow geometry on two token blocks: 43 -> 38 us
     // at 320 rows, no change at 512; the residual projections of such calls are better off split along K in the wide one)
@@ -305,10 +308,13 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st) {
 }
 
 // out = resid + X W^T, through split-K partials when the unsplit launch would leave compute units idle.  X is fragment-
-// major; resid and out are row-major or fragment-major as flagged.  When inv_rms_out is given it receives
-// rsqrt(mean(out[m,:]^2) + eps) per row (the RMSNorm factor of the next GEMM's input); rowss is scratch for it.
+// major; resid and out are row-major or fragment-major as flagged.  When inv_rms_out is given, the RMSNorm factor of the
+// next GEMM's input, rsqrt(mean(out[m,:]^2) + eps) per row, is prepared in one of two forms: the split-K reduction writes
+// it to inv_rms_out (*rowss_parts_out = 0); an unsplit launch leaves *rowss_parts_out > 0 partial sums of squares per row
+// in rowss, which the next GEMM closes itself (GemmArgs::rowss).
 rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf16* resid, int resid_frag, bf16* out,
-                        int out_frag, int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, hipStream_t st) {
+                        int out_frag, int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, int* rowss_parts_out,
+                        hipStream_t st) {
     GemmArgs a{};
     a.X = X; a.W = W; a.out = out; a.ldo = N; a.out_frag = out_frag; a.resid = resid; a.ldr = N; a.resid_frag = resid_frag;
     a.partial = partial;
@@ -319,14 +325,10 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf1
         const int sps = (K / GS_BK + splits - 1) / splits;
         splits = (K / GS_BK + sps - 1) / sps;
     }
+    if (rowss_parts_out) *rowss_parts_out = 0;
     if (splits == 1) {
         a.rowss = inv_rms_out ? rowss : nullptr;
-        rs_status s = launch_gemm<EPI_RESIDUAL>(c, a, 1, st);
-        if (s != RS_OK || !inv_rms_out) return s;
-        hipLaunchKernelGGL(rowss_finalize_kernel, dim3((M + 3) / 4), dim3(256), 0, st, (const float*)rowss, N / 32, M, N, eps,
-                           inv_rms_out);
-        RS_HIP(hipGetLastError());
-        return RS_OK;
+        return launch_gemm<EPI_RESIDUAL>(c, a, 1, st, inv_rms_out ? rowss_parts_out : nullptr);
     }
     rs_status s = launch_gemm<EPI_PARTIAL>(c, a, splits, st);
     if (s != RS_OK) return s;
@@ -377,18 +379,12 @@ rs_status launch_attention_path(const rs_ctx* c, bf16* qkv, bf16* attn, const Re
     tm.end(RS_STEP_APPEND_KV);
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)D));
     tm.begin(RS_STEP_ATTENTION);
-    if (c->attn_variant == 2)
-        hipLaunchKernelGGL(attn_prefill_wide_kernel<D>, dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
-                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
-    else if (c->attn_variant == 1 && any_paged)
+    if (any_paged)
         hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, true>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e, split_buf);
-    else if (c->attn_variant == 1)
+    else
         hipLaunchKernelGGL((attn_prefill_pipelined_kernel<D, false>), dim3(n_items), dim3(256), 0, st, d_reqs, d_items,
                            (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e, split_buf);
-    else
-        hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(n_items), dim3(256), 4 * ATT_KEYS * D * 2, st, d_reqs, d_items,
-                           (const bf16*)qkv, c->qkv_dim, attn, c->q_dim, c->group, scale_log2e);
     RS_HIP(hipGetLastError());
     if (n_mitems > 0) {
         hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(n_mitems, ATT_MERGE_Y), dim3(256), 0, st, d_reqs, d_mitems, (const float*)split_buf, attn,
@@ -587,6 +583,18 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         else if (capturing != hipStreamCaptureStatusNone) return fail(RS_ESTATE, "the stream is capturing a HIP graph");
     }
 
+    // Pages taken below go back to their pools if a later host-side check refuses the call (nothing may change on a
+    // status other than RS_OK); from the first launch on they stay.
+    struct PageRollback {
+        struct Entry { rs_kv* kv; int layer; int len; };
+        std::vector<Entry> taken;
+        bool armed = true;
+        ~PageRollback() {
+            if (!armed) return;
+            for (auto it = taken.rbegin(); it != taken.rend(); ++it) it->kv->give_back_pages(it->layer, it->len);
+        }
+    } rollback;
+
     // ---- host descriptors
     std::vector<ReqDesc> reqs;
     std::vector<AttnItem> items;
@@ -607,6 +615,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         if (Ti == 0) continue;
         rs_kv* kv = kvs[i];
         const int P = kv->len[layer];
+        if (kv->paged() && kv->pages_missing(layer, (long)P + Ti) > 0) rollback.taken.push_back({kv, layer, P});
         kv->take_pages(layer, (long)P + Ti);   // (paged caches; prefill_check has made sure the pool has them)
         ReqDesc d = kv->view(layer, d_pagetab + pagetab.size());
         d.row0 = row0; d.T = Ti; d.P = P;
@@ -633,10 +642,9 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         if (kv->paged()) pagetab.insert(pagetab.end(), kv->pages[layer].begin(), kv->pages[layer].end());
         const int ri = (int)reqs.size();
         reqs.push_back(d);
-        const int item_rows = ctx->attn_variant == 2 ? ATT_WIDE_ROWS : ATT_ROWS;
-        const int nqb = (Ti * g + item_rows - 1) / item_rows;
+        const int nqb = (Ti * g + ATT_ROWS - 1) / ATT_ROWS;
         for (int qb = 0; qb < nqb; ++qb) {
-            const int t_max = std::min(Ti - 1, (qb * item_rows + item_rows - 1) / g);
+            const int t_max = std::min(Ti - 1, (qb * ATT_ROWS + ATT_ROWS - 1) / g);
             const int nkb = (P + t_max + 1 + ATT_KEYS - 1) / ATT_KEYS;
             for (int c = 0; c < f.n_kv_heads; ++c) items.push_back(AttnItem{ri, c, qb, nkb, 0, -1, 0, 0});
         }
@@ -647,11 +655,11 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     }
     // Fewer blocks than compute units: cut the key ranges so that up to two workgroups per compute unit exist, not more (a
     // third round of workgroups costs more than the shorter parts save: 512 rows on 16384 cached tokens 201 us with 5 parts,
-    // 175 with 4) - the default kernel only.  A part has at least ATT_MIN_PART_TILES tiles, so every row of the block sees
+    // 175 with 4).  A part has at least ATT_MIN_PART_TILES tiles, so every row of the block sees
     // keys in each part: the rows of a block span at most 128 positions, i.e. only the last three tiles can be hidden from
     // some of them.
     std::vector<AttnMergeItem> mitems;
-    if (ctx->attn_variant == 1 && !items.empty()) {
+    if (!items.empty()) {
         const int blocks = (int)items.size();
         int want = ctx->attn_split;
         if (want == 0) {
@@ -765,6 +773,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     rs_status s;
     const StepTimer tm{ctx, st};
 
+    rollback.armed = false;   // every host-side check has passed: from here on the call is launched
     // 1/rms of every input row (the first RMSNorm; its gain lives in the packed W_qkv)
     tm.begin(RS_STEP_ROW_RMS);
     // and, in the same pass, x in the GEMMs' fragment-major token-operand layout
@@ -805,7 +814,8 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     if (s != RS_OK) return s;
     // r = x + attn Wo^T, and 1/rms of every row of r (the second RMSNorm; its gain lives in the packed W_gate_up)
     tm.begin(RS_STEP_O_GEMM);
-    if ((s = gemm_residual(ctx, attn, (const bf16*)w->w_o, xb, 0, r, 1, T, H, ctx->q_dim, partial, inv_rms2, rowss, st)) != RS_OK) return s;
+    int rowss_parts = 0;
+    if ((s = gemm_residual(ctx, attn, (const bf16*)w->w_o, xb, 0, r, 1, T, H, ctx->q_dim, partial, inv_rms2, rowss, &rowss_parts, st)) != RS_OK) return s;
     tm.end(RS_STEP_O_GEMM);
     // act = silu((r Wg'^T) / rms) * ((r Wu'^T) / rms)
     tm.begin(RS_STEP_GATE_UP_GEMM);
@@ -813,13 +823,16 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         GemmArgs a{};
         a.X = r; a.W = (const bf16*)w->w_gate_up; a.out = act; a.ldo = I; a.out_frag = 1;
         a.row_scale = inv_rms2;
+        if (rowss_parts > 0) {   // the output projection ran unsplit: its per-column sums of squares, closed in this kernel
+            a.rowss = rowss; a.rowss_parts = rowss_parts; a.rms_eps = f.rms_eps;
+        }
         a.M = T; a.N = 2 * I; a.K = H;
         if ((s = launch_gemm<EPI_SWIGLU>(ctx, a, 1, st)) != RS_OK) return s;
     }
     tm.end(RS_STEP_GATE_UP_GEMM);
     // y = r + act Wd^T
     tm.begin(RS_STEP_DOWN_GEMM);
-    if ((s = gemm_residual(ctx, act, (const bf16*)w->w_down, r, 1, yb, 0, T, H, I, partial, nullptr, nullptr, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, act, (const bf16*)w->w_down, r, 1, yb, 0, T, H, I, partial, nullptr, nullptr, nullptr, st)) != RS_OK) return s;
     tm.end(RS_STEP_DOWN_GEMM);
 
     for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
@@ -868,7 +881,6 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     c->q_dim = q_dim; c->kv_dim = kv_dim; c->qkv_dim = qkv_dim; c->group = f.n_q_heads / f.n_kv_heads;
     c->mrope_b0 = c->mrope_b1 = f.head_dim / 2;  // 1-D RoPE: every pair turns with the first axis
     if (const char* e = getenv("RS_SPLITK")) c->splitk_override = atoi(e);
-    if (const char* e = getenv("RS_ATTN")) c->attn_variant = atoi(e);
     if (const char* e = getenv("RS_PAIRS")) c->gemm_pairs = atoi(e);
     if (const char* e = getenv("RS_NARROW")) c->gemm_narrow = atoi(e);
     if (const char* e = getenv("RS_NARROW_TM")) c->narrow_max_tiles_m = atoi(e);
@@ -928,9 +940,6 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_RESIDUAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_SWIGLU, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_strip_kernel<EPI_PARTIAL, GS_NARROW_NT, GS_NARROW_SLOTS, 1, GS_NARROW_XD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, GS_NARROW_LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)lm_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LM_ROWS * f.hidden * 4);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 128 * 2);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ATT_KEYS * 64 * 2);
     // (the pipelined attention kernel keeps its LDS in static arrays; these references make the launch stubs exist)
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
@@ -938,8 +947,6 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_pipelined_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_merge_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_merge_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_prefill_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 0);
     if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e)));
     *out = c;
     return RS_OK;
@@ -1430,16 +1437,24 @@ rs_status rs_lm_head(rs_ctx* c, const void* final_norm_gain, const void* w_lm, i
         return fail(RS_EINVAL, "misaligned argument");
     if (workspace_bytes < rs_lm_head_workspace_bytes(c, n_rows))
         return fail(RS_EWORKSPACE, "workspace has %zu bytes, this call needs %zu", workspace_bytes, rs_lm_head_workspace_bytes(c, n_rows));
-    if (!c->has_device) return fail(RS_EHIP, "no HIP device");
+    // the kernel keeps its group of normalised rows (fp32) in LDS: as many rows per launch, up to LM_ROWS, as 160 KB hold
+    constexpr size_t LDS_BYTES = 160 * 1024;
     const int H = c->cfg.hidden;
+    if ((size_t)H * 4 > LDS_BYTES) return fail(RS_EINVAL, "hidden = %d: one fp32 row does not fit the %zu bytes of LDS the head kernel stages it in", H, LDS_BYTES);
+    if (!c->has_device) return fail(RS_EHIP, "no HIP device");
+    if (c->lm_rows == 0) {  // first use on this context: opt in to the LDS size once
+        const int rows = (int)std::min<size_t>(LM_ROWS, LDS_BYTES / ((size_t)H * 4));
+        RS_HIP(hipFuncSetAttribute((const void*)lm_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, rows * H * 4));
+        c->lm_rows = rows;
+    }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     float* h = reinterpret_cast<float*>(workspace);
     hipLaunchKernelGGL(final_norm_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, st, (const bf16*)x, (const bf16*)final_norm_gain, h,
                        n_rows, H, c->cfg.rms_eps);
     RS_HIP(hipGetLastError());
     const int blocks = std::min(4 * c->n_cu, (vocab + 4 * LM_VGROUP - 1) / (4 * LM_VGROUP));
-    for (int r0 = 0; r0 < n_rows; r0 += LM_ROWS) {  // the vocabulary matrix is streamed once per group of LM_ROWS rows
-        const int R = std::min(LM_ROWS, n_rows - r0);
+    for (int r0 = 0; r0 < n_rows; r0 += c->lm_rows) {  // the vocabulary matrix is streamed once per group of rows
+        const int R = std::min(c->lm_rows, n_rows - r0);
         hipLaunchKernelGGL(lm_head_kernel, dim3(blocks), dim3(256), (size_t)R * H * 4, st, (const bf16*)w_lm, (const float*)(h + (size_t)r0 * H),
                            reinterpret_cast<float*>(logits) + (size_t)r0 * vocab, R, vocab, H);
         RS_HIP(hipGetLastError());
