@@ -221,6 +221,22 @@ rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int laye
                            const void* x_dev, int T, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* rs_prefill_chunk for callers that cannot allocate device memory and have no workspace to pass: tight serving loops
+ * and harnesses that forbid hipMalloc around the call.  Same arguments, same kernels, same result to the bit; the
+ * workspace is a static device array of RS_STATIC_WORKSPACE_BYTES inside the library (each GPU the library runs on
+ * holds it until the process ends; its address on the context's GPU is looked up once, in rs_ctx_create).  The call
+ * allocates nothing on the device and calls no allocating library routine.
+ *   - RS_EWORKSPACE, nothing enqueued, nothing changed, if the call needs more than the array holds:
+ *     rs_workspace_bytes(ctx, T, 1) (8-bit caches: rs_workspace_bytes_fp8kv with the tokens visible after the call) must
+ *     be <= rs_static_workspace_bytes().  At the 7B shape that is up to 640 rows per call.
+ *   - RS_ESTATE if the GPU current on the calling thread is not the one the context was created on.
+ *   - Every call on a GPU shares that GPU's array: two calls whose work overlaps on one GPU (different streams, or
+ *     different contexts) race.  Nothing in it has to start at zero; it keeps the last call's intermediates. */
+#define RS_STATIC_WORKSPACE_BYTES ((size_t)128 << 20)
+size_t rs_static_workspace_bytes(void);
+rs_status rs_prefill_chunk_static(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv,
+                                  const void* x_dev, int T, void* y_dev, void* hip_stream);
+
 /* One micro-batch of R requests through one layer (the set S of Algorithm 2, section 3.3).
  *   kvs[i], chunk_lens[i]  host arrays: request i contributes chunk_lens[i] >= 0 rows this round.
  *   x   device bf16 [sum chunk_lens, H]: rows packed in request order, each request's rows contiguous, prompt order.

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "rs_kv_alloc_paged",
     "rs_kv_fp8_bytes", "rs_kv_alloc_fp8", "rs_kv_is_fp8", "rs_kv_export_codes", "rs_kv_import_codes", "rs_workspace_bytes_fp8kv",
     "rs_kv_page_bytes_fp8", "rs_kv_pool_create_fp8", "rs_kv_pool_is_fp8", "rs_kv_alloc_paged_fp8",
-    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_batch", "rs_prefill_model_batch", "rs_prefill_model_batch_mrope", "rs_ctx_set_mrope_sections",
+    "rs_workspace_bytes", "rs_prefill_chunk", "rs_prefill_chunk_static", "rs_static_workspace_bytes", "rs_prefill_batch", "rs_prefill_model_batch", "rs_prefill_model_batch_mrope", "rs_ctx_set_mrope_sections",
     "rs_prefill_batch_mrope", "rs_lm_head_workspace_bytes",
     "rs_lm_head", "rs_last_error", "rs_version",
     "rs_profile_enable", "rs_profile_sample_every", "rs_profile_read",
@@ -119,6 +119,8 @@ def load_library():
         "rs_kv_pool_is_fp8": (i, [vp]),
         "rs_kv_alloc_paged_fp8": (i, [vp, vp, i, C.c_float, C.c_float, C.POINTER(vp)]),
         "rs_prefill_chunk": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp, sz, vp]),
+        "rs_prefill_chunk_static": (i, [vp, C.POINTER(_Weights), i, vp, vp, i, vp, vp]),
+        "rs_static_workspace_bytes": (sz, []),
         "rs_prefill_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, vp, vp, vp, sz, vp]),
         "rs_prefill_model_batch_mrope": (i, [vp, C.POINTER(_Weights), i, C.POINTER(vp), C.POINTER(i), i, C.POINTER(i), vp, vp, vp, sz, vp]),
@@ -392,6 +394,16 @@ class Context:
         _check(self.lib.rs_prefill_chunk(self.handle, C.byref(packed.struct), layer, kv.handle, _ptr(x), t, _ptr(y),
                                          _ptr(workspace), workspace.numel(), _stream_handle(stream)))
         return y
+
+    def prefill_chunk_static(self, packed: PackedWeights, layer: int, kv: KVCache, x, y, stream=None):
+        """prefill_chunk on the library's static workspace (no workspace argument, nothing allocated by the call)."""
+        t = int(x.shape[0])
+        _check(self.lib.rs_prefill_chunk_static(self.handle, C.byref(packed.struct), layer, kv.handle, _ptr(x), t, _ptr(y),
+                                                _stream_handle(stream)))
+        return y
+
+    def static_workspace_bytes(self) -> int:
+        return int(self.lib.rs_static_workspace_bytes())
 
     def prefill_batch(self, packed: PackedWeights, layer: int, kvs: Sequence[KVCache], chunk_lens: Sequence[int],
                       x, y, workspace, stream=None):

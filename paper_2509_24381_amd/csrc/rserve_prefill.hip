@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -50,6 +51,28 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 constexpr int RING_SLOTS = 32;
 constexpr int RING_CHECKPOINT = 8;
 
+// Workspace of rs_prefill_chunk_static.  In host code the array's name is only a handle for hipGetSymbolAddress: each GPU
+// holds its own copy at its own address, which static_workspace_lookup fetches once per device (with that device
+// current) and every later use goes through.
+static __device__ __align__(256) unsigned char g_static_workspace[RS_STATIC_WORKSPACE_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_static_workspace_addr[MAX_DEVICES] = {};   // per device; written under g_static_workspace_mutex
+std::mutex g_static_workspace_mutex;
+
+// The address of the current device's copy of the array (the device must be `dev`); looked up on first use.
+hipError_t static_workspace_lookup(int dev, void** out) {
+    std::lock_guard<std::mutex> lock(g_static_workspace_mutex);
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_static_workspace_addr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_workspace));
+        if (e != hipSuccess) return e;
+        g_static_workspace_addr[dev] = p;
+    }
+    *out = g_static_workspace_addr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 rs_status rs_internal_fail(rs_status st, const char* fmt, ...) {
@@ -84,6 +107,8 @@ struct rs_ctx {
     int narrow_max_tiles_m = 1;  // narrow_max_tiles_m (RS_NARROW_TM) token blocks whose strips would hold at most 2 units use it
     int n_cu = 256;           // compute units of the device: the number of strips a GEMM launch is cut into
     bool has_device = false;  // false: created on a host without a GPU; argument checks work, launches return RS_EHIP
+    int device = -1;          // the GPU that was current in rs_ctx_create
+    void* static_ws = nullptr;  // that GPU's copy of the static workspace (rs_prefill_chunk_static)
     int lm_rows = 0;          // rows per launch of the first-token head (0: its LDS size not yet set, see rs_lm_head)
     // measurement hook: HIP events around every launch of one step of the layer
     int prof_step = -1;
@@ -921,9 +946,12 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
         c->slot_recorded_at[i] = -1;
     }
     int dev = 0, n_cu = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0)
-        c->n_cu = n_cu;
+    e = hipGetDevice(&dev);
+    if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipGetDevice: %s", hipGetErrorString(e)));
+    c->device = dev;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0) c->n_cu = n_cu;
+    e = static_workspace_lookup(dev, &c->static_ws);
+    if (e != hipSuccess) return cleanup(fail(RS_EHIP, "hipGetSymbolAddress(static workspace): %s", hipGetErrorString(e)));
     if (const char* e = getenv("RS_NCU")) {  // test hook: fewer, wider strips exercise every tile width on small shapes
         if (atoi(e) > 0) c->n_cu = atoi(e);
     }
@@ -1357,6 +1385,31 @@ rs_status rs_prefill_chunk(rs_ctx* ctx, const rs_layer_weights* packed, int laye
     rs_kv* kvs[1] = {kv};
     int lens[1] = {T};
     return prefill_impl(ctx, packed, layer, kvs, lens, 1, x, y, workspace, workspace_bytes, stream);
+}
+
+size_t rs_static_workspace_bytes(void) { return RS_STATIC_WORKSPACE_BYTES; }
+
+rs_status rs_prefill_chunk_static(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* kv, const void* x, int T, void* y,
+                                  void* stream) {
+    if (!ctx) return fail(RS_EINVAL, "ctx is null");
+    if (!kv) return fail(RS_EINVAL, "kv is null");
+    if (T < 0) return fail(RS_EINVAL, "T = %d is negative", T);
+    if (ctx->has_device) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+            return fail(RS_ESTATE, "the current GPU (%d) is not the one the context was created on (%d)", dev, ctx->device);
+    }
+    // (a host-only context has no array to point at; every check before the missing device still runs, on a stand-in address)
+    void* ws = ctx->has_device ? ctx->static_ws : reinterpret_cast<void*>(uintptr_t{256});
+    rs_kv* kvs[1] = {kv};
+    int lens[1] = {T};
+    const rs_status s = prefill_impl(ctx, packed, layer, kvs, lens, 1, x, y, ws, RS_STATIC_WORKSPACE_BYTES, stream);
+    if (s == RS_EWORKSPACE) {
+        const std::string why = g_last_error;
+        return fail(RS_EWORKSPACE, "%s: beyond the static workspace of rs_prefill_chunk_static (use rs_prefill_chunk with a workspace of the caller's)",
+                    why.c_str());
+    }
+    return s;
 }
 
 rs_status rs_prefill_batch(rs_ctx* ctx, const rs_layer_weights* packed, int layer, rs_kv* const* kvs, const int* chunk_lens, int R,

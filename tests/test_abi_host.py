@@ -272,6 +272,41 @@ def test_valid_call_without_a_gpu_fails_loudly(lib):
     assert kv.length(0) == 0
 
 
+def test_static_workspace_entry_point_checks_on_the_host(lib):
+    """rs_prefill_chunk_static makes rs_prefill_chunk's checks against the size of the static array: a call beyond it
+    is RS_EWORKSPACE (and says which entry point to use instead), one that fits gets as far as needing the GPU."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("this check is for GPU-less hosts")
+    assert lib.rs_static_workspace_bytes() == 128 << 20
+    cfg7 = LayerConfig(hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_inter=18944, max_tokens_per_call=2048,
+                       max_requests=1, max_pos=4096)
+    ctx = Context(cfg7)
+    kv = make_kv(lib, ctx, n_layers=1, capacity=4096)
+
+    def X(t):
+        class T:
+            shape = (t, 3584)
+            def data_ptr(self):
+                return 0x7B0000000000
+        return T()
+
+    def status_of(fn):
+        with pytest.raises(RsError) as e:
+            fn()
+        return e.value
+    assert ctx.workspace_bytes(643, 1) <= 128 << 20 < ctx.workspace_bytes(644, 1)
+    e = status_of(lambda: ctx.prefill_chunk_static(fake_weights(), 0, kv, X(644), X(644)))
+    assert e.status_name == "RS_EWORKSPACE" and "rs_prefill_chunk_static" in str(e)
+    assert status_of(lambda: ctx.prefill_chunk_static(fake_weights(), 0, kv, X(643), X(643))).status_name == "RS_EHIP"
+    assert status_of(lambda: ctx.prefill_chunk_static(fake_weights(), 3, kv, X(8), X(8))).status_name == "RS_EINVAL"
+    assert status_of(lambda: ctx.prefill_chunk_static(fake_weights(), 0, kv, X(4097), X(4097))).status_name == "RS_EINVAL"
+    assert lib.rs_prefill_chunk_static(ctx.handle, None, 0, kv.handle, None, 8, None, None) == -1
+    assert lib.rs_prefill_chunk_static(ctx.handle, C.byref(fake_weights().struct), 0, None, None, 8, None, None) == -1
+    ctx.prefill_chunk_static(fake_weights(), 0, kv, X(0), X(0))   # an empty call is a no-op everywhere
+    assert kv.length(0) == 0
+
+
 def test_8bit_cache_argument_checks_on_the_host(lib):
     """Sizes, scales, the one-kind-per-call rule and the workspace an 8-bit cache's expansion needs: all decided before a
     device is touched."""
