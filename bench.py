@@ -3,7 +3,8 @@
 
 A step is one pass of the whole hot path over the benchmark workload: a synthetic 8192-token multi-image prompt
 (6 images of 1024 embedding rows interleaved with text spans) prefilled in 4 chunks under a 2048-token budget through
-4 stacked 7B-shaped decoder layers, i.e. 16 rs_prefill_chunk calls with the KV prefix growing 0 -> 6144.
+4 stacked 7B-shaped decoder layers, i.e. 4 rs_prefill_model_batch calls of 4 layers each (16 layer passes) with the KV
+prefix growing 0 -> 6144.
 `value` = layer-tokens per second (tokens x layers / time), inputs and weights resident in HBM.
 `--workload 1..5` times one of the other parity workloads the same way (4 = the 16-request ragged micro-batch through
 rs_prefill_batch, 5 = the 72B-shaped layer over a 32768-token prompt); the default, 3, is the headline configuration.

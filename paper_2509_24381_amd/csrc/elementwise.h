@@ -14,10 +14,24 @@
 // positions) from the pinned host buffer the library filled, which the device reads in place, into the workspace: the
 // later kernels of the call then find them in device memory, and no copy command sits between two calls (a runtime copy
 // of a few tens of KB costs a blit kernel of 13 us plus the gaps around it).
+// REDUCE = true is the same pass with the row taken not from x but from the split-K partial planes of the previous
+// layer's down projection (the layers of one rs_prefill_model_batch call): the row is
+// bf16(resid[m, :] + sum_s partial[s][m][:]), summed and rounded exactly as splitk_reduce_residual_kernel does, stored
+// row-major to y (the previous layer's output, this layer's residual input) and fragment-major to dst, and its 1/rms is
+// taken from the rounded values in the same order as from x - so a stack of layers run this way leaves the same bits
+// as the layers called one by one, without the previous layer's reduction kernel and this layer's pass over its output.
+struct ReduceSource {
+    const float* partial;   // [splits][rows][H] fp32
+    int splits;             // 2..4
+    const bf16* resid;      // [rows, H] fragment-major
+    bf16* y;                // [rows, H] row-major
+};
+template <bool REDUCE>
 __global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16* __restrict__ x, bf16* __restrict__ dst,
                                                                      float* __restrict__ inv_rms, int rows, int H, float eps,
                                                                      const uint4* __restrict__ desc_src,
-                                                                     uint4* __restrict__ desc_dst, int desc_chunks) {
+                                                                     uint4* __restrict__ desc_dst, int desc_chunks,
+                                                                     ReduceSource red) {
     // (the copying workgroups come first in the grid: their reads cross the host link, several microseconds each, and
     // should be under way while the row blocks stream; launched last they were the tail of the kernel)
     const int desc_blocks = (desc_chunks + 255) >> 8;
@@ -29,25 +43,52 @@ __global__ __launch_bounds__(256) void rms_and_fragment_major_kernel(const bf16*
     const int r = threadIdx.x >> 5, c = threadIdx.x & 31;
     const int m = ((int)blockIdx.x - desc_blocks) * 8 + r;
     const int mc = min(m, rows - 1);  // threads of rows past the end follow along (their shuffles are needed) and store nothing
-    const char* src = reinterpret_cast<const char*>(x + (size_t)mc * H) + c * 16;
+    const size_t frag_row = ((size_t)(mc >> 5) * (H >> 4) * 2 + c) * 512 + (mc & 31) * 16;   // chunk c of row mc, fragment-major
+    const char* src = REDUCE ? reinterpret_cast<const char*>(red.resid) + frag_row
+                             : reinterpret_cast<const char*>(x + (size_t)mc * H) + c * 16;
+    constexpr size_t SRC_STEP = REDUCE ? 512 : 16;   // bytes from one 16-byte chunk of the row to the next in the source
     char* out = reinterpret_cast<char*>(dst) + ((size_t)(m >> 5) * (H >> 4) * 2 + c) * 512 + (m & 31) * 16;
     float ss = 0.0f;
     const int chunks = H >> 3;  // 16-byte chunks per row; a step covers 32 of them (256 features = 16 k-steps x 2 halves)
-    for (int c0 = 0; c0 < chunks; c0 += 4 * 32) {
-        uint4 v[4];
+    constexpr int U = 4;   // chunks in flight per thread (eight measured no faster for either form)
+    for (int c0 = 0; c0 < chunks; c0 += U * 32) {
+        uint4 v[U];
+        f32x4 part[REDUCE ? U : 1][REDUCE ? 4 : 1][2];   // [chunk in flight][plane][half of the 8 features]
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (c0 + u * 32 + c < chunks) v[u] = ld_global_16(src + (size_t)(c0 + u * 32) * 16);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
             if (c0 + u * 32 + c < chunks) {
-                const bf16x8 h = as_bf16x8(v[u]);
+                v[u] = ld_global_16(src + (size_t)(c0 + u * 32) * SRC_STEP);
+                if constexpr (REDUCE) {
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp)
+                        if (sp < red.splits) {
+                            const float* pp = red.partial + ((size_t)sp * rows + mc) * H + (size_t)(c0 + u * 32 + c) * 8;
+                            part[u][sp][0] = *reinterpret_cast<const f32x4*>(pp);
+                            part[u][sp][1] = *reinterpret_cast<const f32x4*>(pp + 4);
+                        }
+                }
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (c0 + u * 32 + c < chunks) {
+                bf16x8 h = as_bf16x8(v[u]);
+                if constexpr (REDUCE) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float f = bf16_to_f32(h[e]);
+#pragma unroll
+                        for (int sp = 0; sp < 4; ++sp)
+                            if (sp < red.splits) f += part[u][sp][e >> 2][e & 3];
+                        h[e] = f32_to_bf16(f);
+                    }
+                    if (m < rows) st_global_16(reinterpret_cast<char*>(red.y + (size_t)m * H) + (size_t)(c0 + u * 32 + c) * 16, as_uint4(h));
+                }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float f = bf16_to_f32(h[e]);
                     ss += f * f;
                 }
-                if (m < rows) st_global_16(out + (size_t)(c0 + u * 32) * 512, v[u]);
+                if (m < rows) st_global_16(out + (size_t)(c0 + u * 32) * 512, as_uint4(h));
             }
     }
 #pragma unroll

@@ -337,9 +337,17 @@ rs_status launch_gemm(const rs_ctx* c, GemmArgs a, int splits, hipStream_t st, i
 // next GEMM's input, rsqrt(mean(out[m,:]^2) + eps) per row, is prepared in one of two forms: the split-K reduction writes
 // it to inv_rms_out (*rowss_parts_out = 0); an unsplit launch leaves *rowss_parts_out > 0 partial sums of squares per row
 // in rowss, which the next GEMM closes itself (GemmArgs::rowss).
+// With `defer` (the layers of one rs_prefill_model_batch call) a split-K launch leaves its reduction to the next layer's
+// first kernel: *defer then describes the pending sum (splits > 0) and `out` has not been written yet.
+struct PendingReduce {
+    int splits = 0;             // 0: nothing pending
+    const float* partial = nullptr;
+    const bf16* resid = nullptr;   // fragment-major
+    bf16* out = nullptr;           // row-major
+};
 rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf16* resid, int resid_frag, bf16* out,
                         int out_frag, int M, int N, int K, float* partial, float* inv_rms_out, float* rowss, int* rowss_parts_out,
-                        hipStream_t st) {
+                        hipStream_t st, PendingReduce* defer = nullptr) {
     GemmArgs a{};
     a.X = X; a.W = W; a.out = out; a.ldo = N; a.out_frag = out_frag; a.resid = resid; a.ldr = N; a.resid_frag = resid_frag;
     a.partial = partial;
@@ -357,6 +365,10 @@ rs_status gemm_residual(const rs_ctx* c, const bf16* X, const bf16* W, const bf1
     }
     rs_status s = launch_gemm<EPI_PARTIAL>(c, a, splits, st);
     if (s != RS_OK) return s;
+    if (defer && resid_frag && !out_frag && !inv_rms_out) {
+        defer->splits = splits; defer->partial = partial; defer->resid = resid; defer->out = out;
+        return RS_OK;
+    }
     if (M <= 512)  // few rows: a workgroup per row instead of per four
         hipLaunchKernelGGL(splitk_reduce_residual_kernel<4>, dim3(M), dim3(256), 0, st, (const float*)partial, splits, resid, N,
                            resid_frag, out, N, out_frag, M, N, inv_rms_out, eps);
@@ -598,8 +610,12 @@ rs_status prefill_check(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv
 }
 
 // Enqueues one layer's call (arguments already checked by prefill_check) and advances the cache lengths.
+// `pending_in` (layers after the first of rs_prefill_model_batch): the previous layer's down projection left its split-K
+// sum pending; x is then that layer's output buffer, not yet written, and this layer's first kernel produces it.
+// `pending_out`: this layer may leave its own down projection pending in the same way (the next layer follows at once).
 rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_kv* const* kvs, const int* lens, int R, int T,
-                          const void* x, void* y, void* ws, void* stream, const int* positions3 = nullptr) {
+                          const void* x, void* y, void* ws, void* stream, const int* positions3 = nullptr,
+                          const PendingReduce* pending_in = nullptr, PendingReduce* pending_out = nullptr) {
     const rs_layer_cfg& f = ctx->cfg;
     const WorkspaceLayout L = ws_layout(ctx, T, R);
     {   // a call recorded into a HIP graph would replay with stale descriptors: refuse it, before anything changes
@@ -803,9 +819,17 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     tm.begin(RS_STEP_ROW_RMS);
     // and, in the same pass, x in the GEMMs' fragment-major token-operand layout
     const int desc_chunks = (int)(ds.total / 16);
-    hipLaunchKernelGGL(rms_and_fragment_major_kernel, dim3((T + 7) / 8 + (desc_chunks + 255) / 256), dim3(256), 0, st, xb, xf,
-                       inv_rms1, T, H, f.rms_eps, reinterpret_cast<const uint4*>(ctx->pinned_dev[slot]),
-                       reinterpret_cast<uint4*>(wsb + L.desc), desc_chunks);
+    if (pending_in && pending_in->splits > 0) {
+        // (the pending sum reads the previous layer's r and partial planes, which this layer overwrites only later)
+        ReduceSource red{pending_in->partial, pending_in->splits, pending_in->resid, pending_in->out};
+        hipLaunchKernelGGL(rms_and_fragment_major_kernel<true>, dim3((T + 7) / 8 + (desc_chunks + 255) / 256), dim3(256), 0, st, xb, xf,
+                           inv_rms1, T, H, f.rms_eps, reinterpret_cast<const uint4*>(ctx->pinned_dev[slot]),
+                           reinterpret_cast<uint4*>(wsb + L.desc), desc_chunks, red);
+    } else {
+        hipLaunchKernelGGL(rms_and_fragment_major_kernel<false>, dim3((T + 7) / 8 + (desc_chunks + 255) / 256), dim3(256), 0, st, xb, xf,
+                           inv_rms1, T, H, f.rms_eps, reinterpret_cast<const uint4*>(ctx->pinned_dev[slot]),
+                           reinterpret_cast<uint4*>(wsb + L.desc), desc_chunks, ReduceSource{});
+    }
     RS_HIP(hipGetLastError());
     if (use % RING_CHECKPOINT == RING_CHECKPOINT - 1) {
         RS_HIP(hipEventRecord(ctx->slot_done[slot], st));
@@ -857,7 +881,7 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     tm.end(RS_STEP_GATE_UP_GEMM);
     // y = r + act Wd^T
     tm.begin(RS_STEP_DOWN_GEMM);
-    if ((s = gemm_residual(ctx, act, (const bf16*)w->w_down, r, 1, yb, 0, T, H, I, partial, nullptr, nullptr, nullptr, st)) != RS_OK) return s;
+    if ((s = gemm_residual(ctx, act, (const bf16*)w->w_down, r, 1, yb, 0, T, H, I, partial, nullptr, nullptr, nullptr, st, pending_out)) != RS_OK) return s;
     tm.end(RS_STEP_DOWN_GEMM);
 
     for (int i = 0; i < R; ++i) kvs[i]->len[layer] += lens[i];
@@ -1453,10 +1477,16 @@ static rs_status model_batch(rs_ctx* ctx, const rs_layer_weights* packed_layers,
     }
     if (T > 0 && !ctx->has_device) return fail(RS_EHIP, "no HIP device: the context was created on a host without a GPU");
     if (T == 0) return RS_OK;
-    for (int l = 0; l < n_layers; ++l) {  // layer 0 reads x; later layers work on y in place
+    // Layer 0 reads x; later layers work on y in place.  Between two layers the split-K sum of the down projection, the
+    // pass that takes the next layer's norm factors and the copy into its GEMMs' operand layout are one kernel (see
+    // rms_and_fragment_major_kernel<true>): the bits are those of the layers called one by one.
+    PendingReduce pending;
+    for (int l = 0; l < n_layers; ++l) {
+        PendingReduce next;
         const rs_status s = prefill_enqueue(ctx, &packed_layers[l], l, kvs, chunk_lens, R, T, l == 0 ? x : y, y, workspace, stream,
-                                            positions3);
+                                            positions3, l > 0 ? &pending : nullptr, l + 1 < n_layers ? &next : nullptr);
         if (s != RS_OK) return s;
+        pending = next;
     }
     return RS_OK;
 }

@@ -71,12 +71,18 @@ class LayerStack:
         return KVPool(self.ctx, n_pages, fp8=fp8)
 
     def prefill_prompt(self, x_dev, chunks: Sequence[Tuple[int, int]], kv: KVCache, keep_layer_outputs: bool = False):
-        """Runs one request's prompt chunk by chunk through all layers.
+        """Runs one request's prompt chunk by chunk through all layers: one rs_prefill_model_batch call per chunk, or -
+        when every layer's output is wanted - one rs_prefill_chunk call per chunk and layer.
 
         x_dev: bf16 [N, H] device tensor.  Returns the final layer's output [N, H] (and, if asked, every layer's).
         """
         import torch
         n = x_dev.shape[0]
+        if not keep_layer_outputs:   # all layers of a chunk in one call (the same bits as layer by layer)
+            last = torch.empty_like(x_dev)
+            for a, b in chunks:
+                self.ctx.prefill_model_batch(self.layers, [kv], [b - a], x_dev[a:b], last[a:b], self.ws)
+            return last
         outs = [torch.empty_like(x_dev) for _ in range(self.n_layers)] if keep_layer_outputs else None
         last = torch.empty_like(x_dev)
         scratch = torch.empty_like(x_dev)

@@ -550,6 +550,16 @@ def test_workload3_7b_four_layers_8192_budget2048():
     kv = stack.new_cache(n)
     _, outs = stack.prefill_prompt(_dev(x), wl.chunks(), kv, keep_layer_outputs=True)
     torch.cuda.synchronize()
+    # the same prompt with all layers of a chunk in one rs_prefill_model_batch call (the benchmark's launch form: between
+    # two layers the down projection's split-K sum and the next layer's first pass are one kernel): identical bits
+    kv_mb = stack.new_cache(n)
+    y_mb = stack.prefill_prompt(_dev(x), wl.chunks(), kv_mb)
+    torch.cuda.synchronize()
+    assert torch.equal(y_mb, outs[-1]), "model_batch output differs from the layer-by-layer calls"
+    for l in range(wl.n_layers):
+        for ta, tb in zip(kv_mb.export(l), kv.export(l)):
+            assert torch.equal(ta, tb), f"model_batch cache of layer {l} differs from the layer-by-layer calls"
+    del kv_mb, y_mb
     e2e = []
     for l in range(wl.n_layers):
         k, v = kv.export(l)
