@@ -38,8 +38,8 @@ HBM_PEAK_GBS = 8000.0
 # (KiB per dispatch) from the two rocprofv3 --pmc passes summarised, with their date and commands, in
 # profiles/gate_up_gemm_7b_T2048_hbm_traffic_pmc.md, each scaled by what the same counter reads for a plain copy kernel
 # of known size (--copy-calibration).  Algorithmic bytes of the same launch: 363.9e6.
-GATE_UP_FETCH_KIB, GATE_UP_FETCH_SCALE = 466051.5, 2.0
-GATE_UP_WRITE_KIB, GATE_UP_WRITE_SCALE = 151296.0, 1.0
+GATE_UP_FETCH_KIB, GATE_UP_FETCH_SCALE = 421650.6, 2.0
+GATE_UP_WRITE_KIB, GATE_UP_WRITE_SCALE = 75776.0, 1.0
 GATE_UP_TRAFFIC_BYTES = (GATE_UP_FETCH_KIB * GATE_UP_FETCH_SCALE + GATE_UP_WRITE_KIB * GATE_UP_WRITE_SCALE) * 1024
 
 
