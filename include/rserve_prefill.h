@@ -101,7 +101,9 @@ typedef struct rs_kv rs_kv;   /* one request's KV cache over n_layers layers; ho
  *   RS_NCU=n         compute-unit count the GEMM strips are sized for (default: the device's)
  *   RS_NARROW=0      never the GEMM geometry for strips of at most two units;  RS_NARROW_TM=n  use it up to n token blocks
  *   RS_PAIRS=0       never two wavefronts per pair of units in that geometry
- *   RS_ATTN_SPLIT=n  parts every attention block's key range is cut into (1 = never; default: decided per call) */
+ *   RS_ATTN_SPLIT=n  parts every attention block's key range is cut into (1 = never; default: decided per call)
+ *   RS_ATTN_ORDER=plain  attention work items stay in heaviest-first order (default: between one and two items per
+ *                    compute unit, the heaviest run alone on theirs and the others are paired heavy with light) */
 rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out);
 void rs_ctx_destroy(rs_ctx* ctx);
 

@@ -101,6 +101,7 @@ struct rs_ctx {
     hipStream_t last_stream = nullptr;
     int splitk_override = 0;  // RS_SPLITK environment variable (0 = heuristic)
     int mrope_b0 = 0, mrope_b1 = 0;  // rotary pair j turns with axis 0 below b0, axis 1 below b1, axis 2 above (set in rs_ctx_create)
+    int attn_plain_order = 0; // RS_ATTN_ORDER=plain: attention items stay heaviest-first (no pairing by compute unit)
     int attn_split = 0;       // RS_ATTN_SPLIT environment variable: parts a block's key range is cut into (0: decided per call)
     int gemm_pairs = 1;       // RS_PAIRS environment variable: 0 never lets two wavefronts of a GEMM workgroup split a pair of units
     int gemm_narrow = 1;      // RS_NARROW environment variable: 0 never uses the narrow GEMM geometry; otherwise launches of at most
@@ -748,6 +749,22 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
     // heaviest work first: the tail of the launch is then made of short items
     std::stable_sort(items.begin(), items.end(),
                      [](const AttnItem& a, const AttnItem& b) { return a.nkb - a.kb0 > b.nkb - b.kb0; });
+    // Between one and two workgroups per compute unit every item is resident from the first clock, and on an empty chip the
+    // dispatcher hands workgroup k and workgroup k + n_cu to the same compute unit (measured: 448 workgroups of this
+    // footprint leave exactly workgroups 192 .. 255 alone on theirs).  A lone workgroup walks its tiles faster than two that
+    // share the matrix pipe, and a pair lasts as long as both walks together, so the launch ends soonest when the heaviest
+    // items are the lone ones and the rest are paired heavy with light.  Only the order of independent items changes.
+    const int n_items_now = (int)items.size();
+    if (n_items_now > ctx->n_cu && n_items_now <= 2 * ctx->n_cu && !ctx->attn_plain_order) {
+        const int paired = n_items_now - ctx->n_cu, lone = ctx->n_cu - paired;
+        std::vector<AttnItem> placed(items.size());
+        for (int k = 0; k < lone; ++k) placed[paired + k] = items[k];
+        for (int k = 0; k < paired; ++k) {
+            placed[k] = items[lone + k];
+            placed[ctx->n_cu + k] = items[n_items_now - 1 - k];
+        }
+        items.swap(placed);
+    }
 
     if (sizeof(ReqDesc) * reqs.size() > ds.reqs || sizeof(AttnItem) * items.size() > ds.items ||
         sizeof(KVBlockItem) * vbs.size() > ds.vblocks || sizeof(int) * rowpos.size() > ds.rowpos ||
@@ -934,6 +951,7 @@ rs_status rs_ctx_create(const rs_layer_cfg* cfg, rs_ctx** out) {
     if (const char* e = getenv("RS_NARROW")) c->gemm_narrow = atoi(e);
     if (const char* e = getenv("RS_NARROW_TM")) c->narrow_max_tiles_m = atoi(e);
     if (const char* e = getenv("RS_ATTN_SPLIT")) c->attn_split = std::max(0, std::min(atoi(e), ATT_MAX_PARTS));
+    if (const char* e = getenv("RS_ATTN_ORDER")) c->attn_plain_order = strcmp(e, "plain") == 0;
     auto cleanup = [&](rs_status s) { rs_ctx_destroy(c); return s; };
 
     c->slot_bytes = desc_sizes(c, f.max_tokens_per_call, f.max_requests).total;

@@ -311,7 +311,7 @@ def test_row_counts_around_every_wavefront_and_block_boundary(shape_name):
 
 @pytest.mark.parametrize("env", [{"RS_SPLITK": "1"}, {"RS_SPLITK": "2"}, {"RS_SPLITK": "3"},
                                  {"RS_NCU": "1"}, {"RS_NCU": "3"}, {"RS_NCU": "7", "RS_SPLITK": "2"},
-                                 {"RS_ATTN_SPLIT": "1"}, {"RS_ATTN_SPLIT": "3"},
+                                 {"RS_ATTN_SPLIT": "1"}, {"RS_ATTN_SPLIT": "3"}, {"RS_ATTN_ORDER": "plain", "RS_NCU": "7"},
                                  {"RS_NARROW": "0"}, {"RS_NARROW": "1", "RS_NARROW_TM": "8", "RS_NCU": "40"}, {"RS_PAIRS": "0"}])
 def test_alternative_kernel_paths_meet_the_same_bar(env):
     """Other split-K factors of the residual GEMMs, and other numbers of strips (RS_NCU stands in for the device's
@@ -320,7 +320,8 @@ def test_alternative_kernel_paths_meet_the_same_bar(env):
     range, 3 cuts every block with at least 48 key tiles in three and those with at least 32 in two), and the GEMM geometry
     for launches whose strips hold at most two units (RS_NARROW 0: never the narrow one; RS_NARROW_TM 8: also for calls of
     up to 8 token blocks, which with RS_NCU 40 makes strips of one and two units on these shapes; RS_PAIRS 0: never two
-    wavefronts per pair of units) are selectable by
+    wavefronts per pair of units), and the plain order of the attention work items (RS_ATTN_ORDER; the default order, which
+    depends on the compute-unit count, also runs under every RS_NCU value above) are selectable by
     environment variable; each must pass the
     workload-1 parity test on its own (run in a child process because the choice is read once per process)."""
     child_env = dict(os.environ, **env)
