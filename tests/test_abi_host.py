@@ -392,3 +392,14 @@ def test_8bit_page_pools_on_the_host(lib):
     lib.rs_kv_free(kv.handle)
     kv.handle = None
     assert lib.rs_kv_pool_destroy(pool8) == 0 and lib.rs_kv_pool_destroy(pool16) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build is for one GPU: `bench.py --gpus N` with N above 1 exits with status 2 and says why, before it touches a
+    device or prints a JSON line."""
+    import subprocess
+    import sys
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert proc.returncode == 2
+    assert "one GPU" in proc.stderr + proc.stdout
+    assert "{" not in proc.stdout
