@@ -759,9 +759,13 @@ rs_status prefill_enqueue(rs_ctx* ctx, const rs_layer_weights* w, int layer, rs_
         const int paired = n_items_now - ctx->n_cu, lone = ctx->n_cu - paired;
         std::vector<AttnItem> placed(items.size());
         for (int k = 0; k < lone; ++k) placed[paired + k] = items[k];
+        // (the light partners are taken from the tail in runs of one item per KV head, in the head order of the front: the
+        //  blocks of a head then stay on the XCDs, workgroup index mod 8, whose L2 already holds that head's K and V)
+        const int run = ctx->cfg.n_kv_heads;
+        const bool by_head = n_items_now % run == 0 && paired % run == 0;
         for (int k = 0; k < paired; ++k) {
             placed[k] = items[lone + k];
-            placed[ctx->n_cu + k] = items[n_items_now - 1 - k];
+            placed[ctx->n_cu + k] = by_head ? items[n_items_now - run * (k / run + 1) + k % run] : items[n_items_now - 1 - k];
         }
         items.swap(placed);
     }
