@@ -45,13 +45,16 @@ struct KVHeadTiles {
     uint32_t stride;
     const int* pages;
     // MAY_PAGE = false is for kernels launched only when every cache of the call is contiguous: no lookup, and nothing
-    // in the loop that the compiler cannot see to be uniform (the software-pipelined attention kernel loses a tenth of
-    // its speed to the few extra instructions otherwise).
+    // in the loop that the compiler cannot see to be uniform (the software-pipelined attention kernel is about 3 % slower
+    // with the lookup in its loop).
     // The index of a block: may be called long before the address is needed (the lookup's latency then passes unseen).
     template <bool MAY_PAGE = true>
     __device__ __forceinline__ int index_of(int block) const {
         if constexpr (!MAY_PAGE) return block;
-        return pages == nullptr ? block : pages[block];
+        // (a load through the global address space: a generic pointer gives a flat load, which counts on the LDS counter
+        //  as well, and every wait for an LDS fragment while it is in flight then becomes a wait for all of them)
+        typedef const __attribute__((address_space(1))) int* global_ints;
+        return pages == nullptr ? block : ((global_ints)pages)[block];
     }
     // (the index is the same for the whole wavefront; saying so here, where the value is used and not where it was
     // loaded, keeps the address in scalar registers, which the buffer resource of an LDS-DMA load needs)
