@@ -124,9 +124,9 @@ constexpr float ATT_RESCALE_LOG2 = 8.0f;
 
 // ------------------------------------------------------------------------------------------------------------------
 // The kernel is software-pipelined across key tiles.  Per key tile a wavefront has two kinds of work: 32 MFMAs (the two
-// products) and the online softmax on the vector ALU (an exponential per score at a quarter of the ALU rate, plus the
-// scaling, the running maximum, the row sum and the bf16 conversion), about equally long; run one after the other, the
-// matrix pipe idles half of the time.  Here the score product of tile kb+1 is issued between the exponentials of tile
+// products) and the online softmax on the vector ALU (per score a scaling, an exponential - v_exp_f32 issues at 1.2 times
+// the cost of a v_fma_f32 on this chip, measured -, the running maximum, the row sum and half a bf16 conversion: about
+// 600 issue clocks against 1024 of MFMA); run one after the other, the matrix pipe idles a third of the time.  Here the score product of tile kb+1 is issued between the exponentials of tile
 // kb, and the running maximum of tile kb+1 is formed behind the MFMAs of the P.V product of tile kb, so each pipe works
 // in the shadow of the other.  K therefore runs one tile ahead of V: iteration kb reads K(kb+1) and V(kb) from LDS while
 // K(kb+2) and V(kb+1) travel global -> LDS by DMA (buffer_load ... lds: no staging registers) into the buffers that
