@@ -309,6 +309,54 @@ def test_row_counts_around_every_wavefront_and_block_boundary(shape_name):
         np.testing.assert_array_equal(v, v_long[:prior + t])
 
 
+@pytest.mark.parametrize("shape_name", ["tiny", "small128"])
+def test_a_request_alone_and_next_to_another_leaves_the_same_bits(shape_name):
+    """The same request, alone in its calls and next to a second request of one row, must leave the same bits in its
+    cache and in its output rows, chunk after chunk (chunk ends off every block, wavefront and 8-token boundary; qkv bias
+    on, so that rows past a call's last would not come out as zeros), and the V^T places behind the last token of a block
+    must read as zeros although the slab started as NaN patterns."""
+    r = R()
+    shape = synth.TINY if shape_name == "tiny" else synth.LayerShape("small128", 512, 8, 2, 128, 768)
+    w = synth.layer_weights(shape, 911, qkv_bias=True, gains="uniform")
+    cuts = [0, 70, 71, 135, 391, 448, 449, 700]
+    x = synth.prompt_rows([("image", 300), ("text", 400)], shape.hidden, 912)
+    other = synth.prompt_rows([("text", 8)], shape.hidden, 913)
+    stack = r.LayerStack(shape, [w], max_tokens=512, max_requests=2, max_pos=1024, qkv_bias=True)
+    xd, od = r.to_device_bf16(x), r.to_device_bf16(other)
+    kv_a, kv_b, kv_o = stack.new_cache(704), stack.new_cache(704), stack.new_cache(64)
+    for kv in (kv_a, kv_b):
+        kv.slab.view(torch.int16).fill_(0x7FC1)
+    for i, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+        y_a = stack.prefill_batch(0, [kv_a], [b - a], xd[a:b])
+        y_b = stack.prefill_batch(0, [kv_b, kv_o], [b - a, 1], torch.cat([xd[a:b], od[i:i + 1]]))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(r.to_numpy_f32(y_a), r.to_numpy_f32(y_b)[:b - a])
+        assert torch.equal(kv_a.slab.view(torch.int16), kv_b.slab.view(torch.int16)) or _same_up_to(kv_a, kv_b, b, shape)
+        for kv in (kv_a, kv_b):
+            k, v = kv.export(0)
+            assert k.shape[0] == b
+    k_a, v_a = (r.to_numpy_f32(t) for t in kv_a.export(0))
+    k_b, v_b = (r.to_numpy_f32(t) for t in kv_b.export(0))
+    np.testing.assert_array_equal(k_a, k_b)
+    np.testing.assert_array_equal(v_a, v_b)
+    y_ref, k_ref, v_ref = layer_forward(x, LayerParams.from_arrays(shape, w))
+    check("K of the request alone", k_a, k_ref)
+    check("V of the request alone", v_a, v_ref)
+
+
+def _same_up_to(kv_a, kv_b, n, shape):
+    """The two slabs agree wherever the layout defines content: K rows below n, and whole V^T blocks up to the one that
+    holds token n - 1 (zero tail included).  (K rows at and beyond n are never read and keep whatever they held.)"""
+    cap, hkv, d = kv_a.capacity, shape.n_kv_heads, shape.head_dim
+    a = kv_a.slab.view(torch.int16).flatten()[: 2 * hkv * cap * d]
+    b = kv_b.slab.view(torch.int16).flatten()[: 2 * hkv * cap * d]
+    ka, kb = a[: hkv * cap * d].view(hkv, cap, d), b[: hkv * cap * d].view(hkv, cap, d)
+    va, vb = a[hkv * cap * d:].view(hkv, cap // 64, d, 64), b[hkv * cap * d:].view(hkv, cap // 64, d, 64)
+    nb = (n + 63) // 64
+    tail_zero = bool((va[:, nb - 1, :, (n - 1) % 64 + 1:] == 0).all())
+    return bool(torch.equal(ka[:, :n], kb[:, :n]) and torch.equal(va[:, :nb], vb[:, :nb]) and tail_zero)
+
+
 @pytest.mark.parametrize("env", [{"RS_SPLITK": "1"}, {"RS_SPLITK": "2"}, {"RS_SPLITK": "3"},
                                  {"RS_NCU": "1"}, {"RS_NCU": "3"}, {"RS_NCU": "7", "RS_SPLITK": "2"},
                                  {"RS_ATTN_SPLIT": "1"}, {"RS_ATTN_SPLIT": "3"}, {"RS_ATTN_ORDER": "plain", "RS_NCU": "7"},
