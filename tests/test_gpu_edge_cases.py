@@ -357,6 +357,32 @@ def _same_up_to(kv_a, kv_b, n, shape):
     return bool(torch.equal(ka[:, :n], kb[:, :n]) and torch.equal(va[:, :nb], vb[:, :nb]) and tail_zero)
 
 
+def test_attention_item_order_does_not_change_a_bit(monkeypatch):
+    """Between one and two attention blocks per compute unit the host pairs heavy blocks with light ones by compute unit
+    instead of launching them heaviest-first.  Blocks are independent, so the two orders must agree to the bit.  The
+    compute-unit count is a context setting read from the environment when the context is created: 7 here, so that the
+    12 blocks of a 384-row chunk (6 blocks of 128 stacked rows x 2 KV heads) fall between 7 and 14."""
+    r = R()
+    shape = synth.TINY
+    w = synth.layer_weights(shape, 921, gains="uniform")
+    x = r.to_device_bf16(synth.prompt_rows([("image", 500), ("text", 268)], shape.hidden, 922))
+    outs = []
+    for order in ("plain", None):
+        monkeypatch.setenv("RS_NCU", "7")
+        if order:
+            monkeypatch.setenv("RS_ATTN_ORDER", order)
+        else:
+            monkeypatch.delenv("RS_ATTN_ORDER", raising=False)
+        stack = r.LayerStack(shape, [w], max_tokens=384, max_requests=1, max_pos=1024)
+        kv = stack.new_cache(768)
+        y = stack.prefill_prompt(x, [(0, 384), (384, 768)], kv)
+        torch.cuda.synchronize()
+        outs.append(r.to_numpy_f32(y))
+    np.testing.assert_array_equal(outs[0], outs[1])
+    y_ref, _, _ = layer_forward(r.to_numpy_f32(x), LayerParams.from_arrays(shape, w))
+    check("paired order Y", outs[1], y_ref)
+
+
 @pytest.mark.parametrize("env", [{"RS_SPLITK": "1"}, {"RS_SPLITK": "2"}, {"RS_SPLITK": "3"},
                                  {"RS_NCU": "1"}, {"RS_NCU": "3"}, {"RS_NCU": "7", "RS_SPLITK": "2"},
                                  {"RS_ATTN_SPLIT": "1"}, {"RS_ATTN_SPLIT": "3"}, {"RS_ATTN_ORDER": "plain", "RS_NCU": "7"},
